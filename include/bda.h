@@ -1,0 +1,164 @@
+/*
+ * bda.h -- C ABI of the Basis-Decomposed (BD) key/value up-projection library for AMD MI355X.
+ *
+ * BD Attention ("Accelerating Attention with Basis Decomposition") replaces, per attention head h,
+ * the d_c x d_h key (or value) projection W_h by W_h W_h[B,:]^{-1}, where B is a contiguous window
+ * of d_h latent dimensions shared by all heads.  The d_h basis rows become the identity, so only
+ * the (d_c - d_h) x d_h block C_h is stored; the inverse is absorbed by the query (or output) side.
+ * At run time each head computes  out_h = c[:, B] + c[:, Bbar] C_h.
+ *
+ * Conventions
+ *   - All matrices are row-major; every leading dimension (ld*) counts ELEMENTS, not bytes.
+ *   - "host" pointers are read/written by the CPU inside the call; "device" pointers are HIP device
+ *     memory owned by the caller (for example PyTorch tensors).  The device entry points enqueue
+ *     work on `stream` (a hipStream_t passed as void*, NULL = the default stream), never
+ *     synchronise, never allocate and never free.  Small host arrays (H, basis_offset) are copied
+ *     into the kernel arguments before the call returns.
+ *   - Return value: BDA_OK (0) or a negative bda_status; bda_last_error() then describes the
+ *     failure (thread-local).  No exception or abort crosses this boundary.
+ *   - T = 0 (no tokens) is a successful no-op.  Outputs must not overlap inputs, except where a
+ *     function says otherwise.
+ */
+#ifndef BDA_H
+#define BDA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BDA_F32 = 0,
+    BDA_F16 = 1,
+    BDA_BF16 = 2,
+    BDA_F64 = 3 /* only as store_dtype of the prepare calls: "do not round" */
+} bda_dtype;
+
+typedef enum {
+    BDA_BASIS_FIRST = 0,         /* B = first d_h latent dimensions (row-first / col-first BD) */
+    BDA_BASIS_LAST = 1,          /* B = last d_h latent dimensions */
+    BDA_BASIS_RESIDUAL_MIN = 2,  /* first or last, whichever has the smaller mean residual */
+    BDA_BASIS_OFFSET_SEARCH = 3, /* any window starting at a multiple of 16, or the last window */
+    BDA_BASIS_EXPLICIT = 4       /* the caller names the window start */
+} bda_basis_mode;
+
+typedef enum {
+    BDA_SIDE_NONE = 0,
+    BDA_SIDE_Q = 1, /* companion is W_q (d_side x H d_h): head block h becomes W_q^h W_h[B,:]^T */
+    BDA_SIDE_O = 2  /* companion is W_o (H d_h x d_side): head block h becomes W_h[B,:] W_o^h   */
+} bda_side;
+
+typedef enum {
+    BDA_OK = 0,
+    BDA_EINVAL = -1,    /* NULL pointer, bad dimension, ld too small, offset out of range, overlap */
+    BDA_EALIGN = -2,    /* reserved: every alignment is currently served (slow path if needed)    */
+    BDA_EDTYPE = -3,    /* dtype / out_dtype combination not supported                             */
+    BDA_ESINGULAR = -4, /* a basis block W_h[B,:] is numerically singular (prepare only)           */
+    BDA_EHIP = -5       /* a HIP runtime call failed                                               */
+} bda_status;
+
+#define BDA_MAX_GROUPS 8
+
+/*
+ * Offline preparation of one projection (Algorithm "BD Attention Preparation (QK)" for keys with
+ * its query companion; Appendix "BD for VO in MHA" for values with their output companion;
+ * Algorithm "BD Decomposition (Row)" for the window choice).  Host, float64, synchronous.
+ *
+ *   W         host, d_c x (H d_h), ld = ldw: dense projection, head h in columns [h d_h, (h+1) d_h).
+ *   side      host or NULL: companion weight (see bda_side); d_side = its free dimension
+ *             (rows of W_q, columns of W_o); ld = ld_side.
+ *   mode, explicit_offset   how the basis window B = [offset, offset + d_h) is chosen.  The
+ *             residual that ranks windows is the Frobenius reconstruction error of the BD form
+ *             after C (and the companion) have been rounded to `store_dtype`, averaged over
+ *             heads; ties keep the earlier candidate (first before last); NaN counts as +inf.
+ *             With a companion the reconstructed matrix is the per-head product (W_q^h W_h^T or
+ *             W_h W_o^h); without one it is W_h itself.
+ *   C_out     host, (d_c - d_h) x (H d_h) contiguous float64: C_h = W_h[Bbar,:] W_h[B,:]^{-1},
+ *             heads side by side (the layout of C_qk / C_vo in Algorithm "BD Attention Inference").
+ *   side_out  host or NULL, same shape as `side`, contiguous float64.
+ *   basis_offset_out   the chosen window start (0 = first, d_c - d_h = last).
+ *   resid_out NULL or 3 doubles: mean residual of the first window, of the last window, and of
+ *             the chosen window (NaN where a window was not evaluated).
+ * Errors: BDA_EINVAL, BDA_ESINGULAR (message names the head and window).
+ */
+int bda_prepare(const double* W, int64_t ldw, int d_c, int H, int d_h,
+                const double* side, int64_t ld_side, int d_side, bda_side side_kind,
+                bda_basis_mode mode, int explicit_offset, bda_dtype store_dtype,
+                double* C_out, double* side_out, int* basis_offset_out, double* resid_out);
+
+/*
+ * Offline preparation of a BD linear layer (Section "BD for Linear Layer"): column BD of
+ * W = U V with U d_in x r, V r x d_out (both host, contiguous float64).
+ *   Uprime_out  d_in x r:        U V[:, B]                    (replaces U)
+ *   C_out       r x (d_out - r): V[:, B]^{-1} V[:, Bbar]      (replaces V)
+ * mode: FIRST, LAST or RESIDUAL_MIN (B = first or last r output columns).  resid_out as above.
+ */
+int bda_prepare_lowrank(const double* U, const double* V, int d_in, int r, int d_out,
+                        bda_basis_mode mode, bda_dtype store_dtype,
+                        double* Uprime_out, double* C_out, int* basis_offset_out,
+                        double* resid_out);
+
+/*
+ * Run-time BD projection, steps 2-3 of Algorithm "BD Attention Inference" (Eq. qk_bd_merge and
+ * the V' equation of Appendix "BD for VO in MHA"), all heads of all groups in one launch:
+ *
+ *     out[t, col0_g + h d_h + j] = c[t, off_g + j] + sum_{k in Bbar_g} c[t, k] C[rank(k), col]
+ *
+ *   c       device, T x d_c, ld = ldc, element type `dtype`.
+ *   G, H, basis_offset   host: G <= BDA_MAX_GROUPS groups (for example K blocks then V blocks);
+ *           group g has H[g] heads and its own window start basis_offset[g] in [0, d_c - d_h];
+ *           groups occupy consecutive output columns.
+ *   C       device, (d_c - d_h) x N, N = sum_g H[g] d_h, ld = ldC, element type `dtype`;
+ *           row i multiplies the i-th latent dimension outside the group's window (ascending).
+ *   out     device, T x N, ld = ld_out, element type `out_dtype` (= dtype, or BDA_F32).
+ * Products are accumulated in float32 (fp16/bf16 inputs use MFMA), the identity slice is added in
+ * float32, and each output is rounded once (nearest even) when stored.  The MFMA path needs 16-byte
+ * aligned pointers, ld's and basis offsets that are multiples of 8 elements, d_c a multiple of 8
+ * and d_h a multiple of 32; anything else (and BDA_F32 inputs) runs a slower general kernel with
+ * the same result contract.
+ * Errors: BDA_EINVAL, BDA_EDTYPE, BDA_EHIP.
+ */
+int bda_kv_project(const void* c, int64_t ldc, int64_t T, int d_c, int d_h,
+                   int G, const int* H, const int* basis_offset,
+                   const void* C, int64_t ldC, void* out, int64_t ld_out,
+                   bda_dtype dtype, bda_dtype out_dtype, void* stream);
+
+/*
+ * Dense comparator, steps 2-3 of Algorithm "MHA Inference": out = c W with the full d_c-long
+ * contraction, from the same kernel family.  W: device, d_c x N, ld = ldW.
+ */
+int bda_dense_project(const void* c, int64_t ldc, int64_t T, int d_c,
+                      const void* W, int64_t ldW, int64_t N,
+                      void* out, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
+                      void* stream);
+
+/*
+ * BD linear layer (Section "BD for Linear Layer"):  h = x Uprime,  out = [h, h C]  (basis_offset
+ * = 0) or out = [h C, h] (basis_offset = d_out - r).  h is written to its r output columns in
+ * `dtype` and the second product reads it back from there, so no workspace is needed.
+ *   x device T x d_in (ldx); Uprime device d_in x r contiguous; C device r x (d_out - r)
+ *   contiguous; out device T x d_out (ld_out); all of element type `dtype`.
+ */
+int bda_lowrank_linear(const void* x, int64_t ldx, int64_t T, int d_in, int r, int d_out,
+                       int basis_offset, const void* Uprime, const void* C,
+                       void* out, int64_t ld_out, bda_dtype dtype, void* stream);
+
+/*
+ * Tuning / testing hook: which MFMA tile the fp16/bf16 kernels use.  0 = automatic (default: the
+ * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256.
+ * Process-wide; returns the previous policy, or BDA_EINVAL.  Results do not depend on it beyond
+ * float32 summation order inside a tile (none: the order over k is the same for every tile shape).
+ */
+int bda_set_tile_policy(int policy);
+
+/* Message of the last failing call on this thread; never NULL ("" if none). */
+const char* bda_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int bda_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BDA_H */

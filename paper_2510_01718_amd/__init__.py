@@ -1,0 +1,14 @@
+"""BD Attention K/V up-projection for AMD MI355X: thin Python binding over the C-ABI library.
+
+Every step of the path runs in the HIP kernels of libbda.so; this package only marshals
+arguments (see `binding`).  Importing it never builds anything; `load()` raises if the library
+has not been built (`python -m paper_2510_01718_amd.build`).
+"""
+from .binding import (  # noqa: F401
+    BDA_F32, BDA_F16, BDA_BF16, BDA_F64,
+    BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT,
+    SIDE_NONE, SIDE_Q, SIDE_O,
+    BdaError, load, lib_path, exported_symbols,
+    bda_prepare, bda_prepare_lowrank, bda_kv_project, bda_dense_project, bda_lowrank_linear,
+    bda_set_tile_policy, bda_last_error, bda_version,
+)

@@ -1,0 +1,185 @@
+"""ctypes binding of libbda.so: same names as the C ABI (include/bda.h), argument marshalling only.
+
+Host calls (`bda_prepare*`) take and return numpy float64 arrays.  Device calls take anything that
+exposes `data_ptr()` (PyTorch tensors on the GPU) or a raw integer device address, plus explicit
+sizes; they enqueue on the given stream (an integer hipStream_t, e.g.
+`torch.cuda.current_stream().cuda_stream`; 0 = default stream) and return nothing.
+A non-zero status raises BdaError with the library's message.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+BDA_F32, BDA_F16, BDA_BF16, BDA_F64 = 0, 1, 2, 3
+BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT = 0, 1, 2, 3, 4
+SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
+
+EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_kv_project", "bda_dense_project",
+           "bda_lowrank_linear", "bda_set_tile_policy", "bda_last_error", "bda_version")
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_lib = None
+
+
+class BdaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"bda status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "libbda.so")
+
+
+def load():
+    """Loads libbda.so; fails loudly if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is not built; run `python -m paper_2510_01718_amd.build` (needs hipcc)")
+    lib = ctypes.CDLL(path)
+    c_int, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+    dp = ctypes.POINTER(ctypes.c_double)
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.bda_prepare.restype = c_int
+    lib.bda_prepare.argtypes = [dp, i64, c_int, c_int, c_int, dp, i64, c_int, c_int, c_int, c_int,
+                                c_int, dp, dp, ip, dp]
+    lib.bda_prepare_lowrank.restype = c_int
+    lib.bda_prepare_lowrank.argtypes = [dp, dp, c_int, c_int, c_int, c_int, c_int, dp, dp, ip, dp]
+    lib.bda_kv_project.restype = c_int
+    lib.bda_kv_project.argtypes = [vp, i64, i64, c_int, c_int, c_int, ip, ip, vp, i64, vp, i64,
+                                   c_int, c_int, vp]
+    lib.bda_dense_project.restype = c_int
+    lib.bda_dense_project.argtypes = [vp, i64, i64, c_int, vp, i64, i64, vp, i64, c_int, c_int, vp]
+    lib.bda_lowrank_linear.restype = c_int
+    lib.bda_lowrank_linear.argtypes = [vp, i64, i64, c_int, c_int, c_int, c_int, vp, vp, vp, i64,
+                                       c_int, vp]
+    lib.bda_set_tile_policy.restype = c_int
+    lib.bda_set_tile_policy.argtypes = [c_int]
+    lib.bda_last_error.restype = ctypes.c_char_p
+    lib.bda_last_error.argtypes = []
+    lib.bda_version.restype = c_int
+    lib.bda_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def exported_symbols() -> Tuple[str, ...]:
+    lib = load()
+    return tuple(name for name in EXPORTS if hasattr(lib, name))
+
+
+def bda_last_error() -> str:
+    return load().bda_last_error().decode()
+
+
+def bda_version() -> int:
+    return int(load().bda_version())
+
+
+def bda_set_tile_policy(policy: int) -> int:
+    prev = int(load().bda_set_tile_policy(int(policy)))
+    if prev < 0:
+        raise BdaError(prev, bda_last_error())
+    return prev
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise BdaError(status, bda_last_error())
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _dp(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr()) or None
+    return int(x) or None
+
+
+def _int_array(v: Sequence[int]):
+    return (ctypes.c_int * len(v))(*[int(i) for i in v])
+
+
+def bda_prepare(W: np.ndarray, d_c: int, H: int, d_h: int, side: Optional[np.ndarray] = None,
+                side_kind: int = SIDE_NONE, mode: int = BASIS_FIRST, explicit_offset: int = 0,
+                store_dtype: int = BDA_F64, want_resid: bool = False):
+    """Returns (C, side_out or None, basis_offset, resid or None); see include/bda.h."""
+    lib = load()
+    W = _f64(W)
+    K, N = d_c - d_h, H * d_h
+    C = np.empty((max(K, 0), N), dtype=np.float64)
+    side_c, side_out, d_side, ld_side = None, None, 0, 0
+    if side is not None:
+        side_c = _f64(side)
+        side_out = np.empty_like(side_c)
+        d_side = side_c.shape[0] if side_kind == SIDE_Q else side_c.shape[1]
+        ld_side = side_c.shape[1]
+    off = ctypes.c_int(-1)
+    resid = np.full(3, np.nan) if want_resid else None
+    _check(lib.bda_prepare(_dp(W), W.shape[1] if W.ndim == 2 else 0, d_c, H, d_h, _dp(side_c),
+                           ld_side, d_side, side_kind, mode, explicit_offset, store_dtype,
+                           _dp(C), _dp(side_out), ctypes.byref(off), _dp(resid)))
+    return C, side_out, int(off.value), resid
+
+
+def bda_prepare_lowrank(U: np.ndarray, V: np.ndarray, mode: int = BASIS_FIRST,
+                        store_dtype: int = BDA_F64, want_resid: bool = False):
+    """Returns (Uprime, C, basis_offset, resid or None)."""
+    lib = load()
+    U, V = _f64(U), _f64(V)
+    d_in, r = U.shape
+    d_out = V.shape[1]
+    if V.shape[0] != r:
+        raise ValueError("U is d_in x r and V must be r x d_out")
+    Up = np.empty((d_in, r), dtype=np.float64)
+    C = np.empty((r, max(d_out - r, 0)), dtype=np.float64)
+    off = ctypes.c_int(-1)
+    resid = np.full(3, np.nan) if want_resid else None
+    _check(lib.bda_prepare_lowrank(_dp(U), _dp(V), d_in, r, d_out, mode, store_dtype, _dp(Up),
+                                   _dp(C), ctypes.byref(off), _dp(resid)))
+    return Up, C, int(off.value), resid
+
+
+def bda_kv_project(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],
+                   basis_offset: Sequence[int], C, ldC: int, out, ld_out: int, dtype: int,
+                   out_dtype: Optional[int] = None, stream: int = 0) -> None:
+    lib = load()
+    G = len(H)
+    if len(basis_offset) != G:
+        raise ValueError("H and basis_offset must have one entry per group")
+    _check(lib.bda_kv_project(_ptr(c), ldc, T, d_c, d_h, G, _int_array(H), _int_array(basis_offset),
+                              _ptr(C), ldC, _ptr(out), ld_out, dtype,
+                              dtype if out_dtype is None else out_dtype, stream or None))
+
+
+def bda_dense_project(c, ldc: int, T: int, d_c: int, W, ldW: int, N: int, out, ld_out: int,
+                      dtype: int, out_dtype: Optional[int] = None, stream: int = 0) -> None:
+    lib = load()
+    _check(lib.bda_dense_project(_ptr(c), ldc, T, d_c, _ptr(W), ldW, N, _ptr(out), ld_out, dtype,
+                                 dtype if out_dtype is None else out_dtype, stream or None))
+
+
+def bda_lowrank_linear(x, ldx: int, T: int, d_in: int, r: int, d_out: int, basis_offset: int,
+                       Uprime, C, out, ld_out: int, dtype: int, stream: int = 0) -> None:
+    lib = load()
+    _check(lib.bda_lowrank_linear(_ptr(x), ldx, T, d_in, r, d_out, basis_offset, _ptr(Uprime),
+                                  _ptr(C), _ptr(out), ld_out, dtype, stream or None))

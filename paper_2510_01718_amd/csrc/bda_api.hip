@@ -1,0 +1,251 @@
+// Device entry points of libbda: argument validation, tile-grid construction and kernel launch.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <mutex>
+
+#include "bda_gemm_kernels.hpp"
+#include "bda_internal.h"
+
+namespace bda {
+namespace {
+
+std::atomic<int> g_tile_policy{0};
+
+struct Span {
+    const char* lo;
+    const char* hi;
+};
+
+Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld, size_t esz)
+{
+    const char* b = (const char*)p;
+    if (rows <= 0 || cols <= 0) return {b, b};
+    return {b, b + ((rows - 1) * ld + cols) * (int64_t)esz};
+}
+
+bool overlaps(Span a, Span b) { return a.lo < b.hi && b.lo < a.hi; }
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+template <typename K>
+int set_max_lds(K kernel, int bytes, std::once_flag& flag)
+{
+    hipError_t err = hipSuccess;
+    std::call_once(flag, [&] {
+        err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    });
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(err));
+}
+
+template <typename X, typename OutT, int TT, int TN>
+int launch_mfma(GemmArgs& a, hipStream_t st)
+{
+    static std::once_flag once;
+    constexpr int lds = 2 * (64 * TT + 64 * TN) * kRowBytes;
+    auto kern = gemm_mfma_kernel<X, OutT, TT, TN>;
+    if (int rc = set_max_lds(kern, lds, once)) return rc;
+    hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(256), lds, st, a);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
+template <typename InT, typename OutT>
+int launch_general(GemmArgs& a, int64_t N_total, hipStream_t st)
+{
+    hipLaunchKernelGGL((gemm_general_kernel<InT, OutT>), dim3(a.n_tiles, a.m_tiles), dim3(256), 0, st, a, N_total);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
+// Fills the per-group tile tables for column tiles of width bn and token tiles of height bt.
+void build_tiles(GemmArgs& a, int G, const int64_t* group_cols, int bt, int bn)
+{
+    a.n_groups = G;
+    a.tile_start[0] = 0;
+    a.col_start[0] = 0;
+    for (int g = 0; g < G; ++g) {
+        a.tile_start[g + 1] = a.tile_start[g] + (int)((group_cols[g] + bn - 1) / bn);
+        a.col_start[g + 1] = a.col_start[g] + group_cols[g];
+    }
+    a.n_tiles = a.tile_start[G];
+    a.m_tiles = (int)((a.M + bt - 1) / bt);
+}
+
+// Shape of the block of tiles one die works on at a time: sm x sn = slots, as square as the tile
+// grid allows, so that the die's L2 holds few distinct token and weight tiles.
+void choose_super(GemmArgs& a, int slots)
+{
+    auto pow2ceil = [](int v) { int p = 1; while (p < v) p *= 2; return p; };
+    const int mcap = pow2ceil(a.m_tiles), ncap = pow2ceil(a.n_tiles);
+    int sm = slots >= 64 ? 8 : 4;
+    while (sm > 1 && sm > mcap) sm /= 2;                       // no slots for missing token tiles
+    while (slots / sm > ncap && sm * 2 <= mcap) sm *= 2;       // nor for missing column tiles
+    a.sm = sm;
+    a.sn = slots / sm;
+}
+
+// Common launcher.  a.A/B/D, lda/ldb/ldd, M, K, d_h, a_skip, ident and a_off[] are set by the caller.
+int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_dtype, hipStream_t st)
+{
+    int64_t N_total = 0;
+    for (int g = 0; g < G; ++g) N_total += group_cols[g];
+    if (a.M == 0 || N_total == 0) return BDA_OK;
+
+    bool fast = (dtype == BDA_F16 || dtype == BDA_BF16) && a.K > 0;
+    const size_t out_sz = dtype_size(out_dtype);
+    fast = fast && aligned(a.A, 16) && aligned(a.B, 16) && aligned(a.D, out_sz == 4 ? 16 : 8);
+    fast = fast && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldd % 8 == 0 && a.K % 8 == 0 && a.a_skip % 8 == 0;
+    if (a.ident) fast = fast && a.d_h % 32 == 0;   // one 32-column MFMA tile never straddles two heads
+    // 32-bit buffer offsets: a 256-row tile must span less than 2 GiB in each operand
+    const int64_t max_ld = (int64_t)1 << 21;
+    fast = fast && a.lda < max_ld && a.ldd < max_ld && a.ldb < max_ld && (int64_t)a.K * a.ldb * 2 < ((int64_t)1 << 31);
+    for (int g = 0; g < G; ++g) fast = fast && a.a_off[g] % 8 == 0 && group_cols[g] % 8 == 0;
+
+    if (fast) {
+        // big tiles when they still fill the chip, otherwise 128 x 128 tiles with two workgroups
+        // per compute unit
+        const int64_t mt256 = (a.M + 255) / 256;
+        int64_t nt256 = 0;
+        for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
+        const int policy = g_tile_policy.load();
+        const bool big = policy == 2 || (policy == 0 && mt256 * nt256 >= 192);
+        if (big) {
+            build_tiles(a, G, group_cols, 256, 256);
+            choose_super(a, kSlotsPerXcd);
+        } else {
+            build_tiles(a, G, group_cols, 128, 128);
+            choose_super(a, 2 * kSlotsPerXcd);
+        }
+#define BDA_LAUNCH(X, O)                                      \
+    return big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
+        if (dtype == BDA_F16 && out_dtype == BDA_F16) { BDA_LAUNCH(F16, uint16_t); }
+        if (dtype == BDA_F16 && out_dtype == BDA_F32) { BDA_LAUNCH(F16, float); }
+        if (dtype == BDA_BF16 && out_dtype == BDA_BF16) { BDA_LAUNCH(BF16, uint16_t); }
+        if (dtype == BDA_BF16 && out_dtype == BDA_F32) { BDA_LAUNCH(BF16, float); }
+#undef BDA_LAUNCH
+        return fail(BDA_EDTYPE, "unsupported dtype/out_dtype pair %d/%d", dtype, out_dtype);
+    }
+    build_tiles(a, G, group_cols, 64, 64);
+    a.sm = a.sn = 1;
+    if (a.m_tiles > 65535) return fail(BDA_EINVAL, "general kernel: T too large (%lld)", (long long)a.M);
+    if (dtype == BDA_F32 && out_dtype == BDA_F32) return launch_general<float, float>(a, N_total, st);
+    if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_general<RawF16, RawF16>(a, N_total, st);
+    if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_general<RawF16, float>(a, N_total, st);
+    if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_general<RawBF16, RawBF16>(a, N_total, st);
+    if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_general<RawBF16, float>(a, N_total, st);
+    return fail(BDA_EDTYPE, "unsupported dtype/out_dtype pair %d/%d", dtype, out_dtype);
+}
+
+int check_dtypes(const char* fn, int dtype, int out_dtype)
+{
+    if (dtype != BDA_F32 && dtype != BDA_F16 && dtype != BDA_BF16) return fail(BDA_EDTYPE, "%s: bad dtype %d", fn, dtype);
+    if (out_dtype != dtype && out_dtype != BDA_F32) return fail(BDA_EDTYPE, "%s: out_dtype must equal dtype or be BDA_F32 (got %d/%d)", fn, dtype, out_dtype);
+    return BDA_OK;
+}
+
+}  // namespace
+}  // namespace bda
+
+using namespace bda;
+
+extern "C" int bda_set_tile_policy(int policy)
+{
+    clear_error();
+    if (policy < 0 || policy > 2) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0, 1 or 2");
+    return g_tile_policy.exchange(policy);
+}
+
+extern "C" int bda_kv_project(const void* c, int64_t ldc, int64_t T, int d_c, int d_h, int G,
+                              const int* H, const int* basis_offset, const void* C, int64_t ldC,
+                              void* out, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
+                              void* stream)
+{
+    clear_error();
+    if (int rc = check_dtypes("bda_kv_project", dtype, out_dtype)) return rc;
+    if (T < 0 || d_c <= 0 || d_h <= 0 || d_h >= d_c) return fail(BDA_EINVAL, "bda_kv_project: need T >= 0 and 0 < d_h < d_c (T=%lld d_c=%d d_h=%d)", (long long)T, d_c, d_h);
+    if (G <= 0 || G > BDA_MAX_GROUPS || !H || !basis_offset) return fail(BDA_EINVAL, "bda_kv_project: need 1 <= G <= %d and non-NULL H, basis_offset", BDA_MAX_GROUPS);
+    int64_t N = 0;
+    int64_t cols[BDA_MAX_GROUPS];
+    for (int g = 0; g < G; ++g) {
+        if (H[g] <= 0) return fail(BDA_EINVAL, "bda_kv_project: H[%d]=%d", g, H[g]);
+        if (basis_offset[g] < 0 || basis_offset[g] > d_c - d_h) return fail(BDA_EINVAL, "bda_kv_project: basis_offset[%d]=%d outside [0, %d]", g, basis_offset[g], d_c - d_h);
+        cols[g] = (int64_t)H[g] * d_h;
+        N += cols[g];
+    }
+    if (T == 0) return BDA_OK;
+    if (!c || !C || !out) return fail(BDA_EINVAL, "bda_kv_project: NULL device pointer");
+    if (ldc < d_c || ldC < N || ld_out < N) return fail(BDA_EINVAL, "bda_kv_project: leading dimension too small (ldc=%lld ldC=%lld ld_out=%lld, d_c=%d N=%lld)", (long long)ldc, (long long)ldC, (long long)ld_out, d_c, (long long)N);
+    const size_t esz = dtype_size(dtype), osz = dtype_size(out_dtype);
+    const int K = d_c - d_h;
+    Span so = span_of(out, T, N, ld_out, osz);
+    if (overlaps(so, span_of(c, T, d_c, ldc, esz)) || overlaps(so, span_of(C, K, N, ldC, esz)))
+        return fail(BDA_EINVAL, "bda_kv_project: out overlaps an input");
+    GemmArgs a{};
+    a.A = c; a.B = C; a.D = out;
+    a.lda = ldc; a.ldb = ldC; a.ldd = ld_out;
+    a.M = T; a.K = K; a.d_h = d_h; a.a_skip = d_h; a.ident = 1;
+    for (int g = 0; g < G; ++g) a.a_off[g] = basis_offset[g];
+    return run_gemm(a, G, cols, dtype, out_dtype, (hipStream_t)stream);
+}
+
+extern "C" int bda_dense_project(const void* c, int64_t ldc, int64_t T, int d_c, const void* W,
+                                 int64_t ldW, int64_t N, void* out, int64_t ld_out, bda_dtype dtype,
+                                 bda_dtype out_dtype, void* stream)
+{
+    clear_error();
+    if (int rc = check_dtypes("bda_dense_project", dtype, out_dtype)) return rc;
+    if (T < 0 || d_c <= 0 || N <= 0) return fail(BDA_EINVAL, "bda_dense_project: need T >= 0, d_c > 0, N > 0");
+    if (T == 0) return BDA_OK;
+    if (!c || !W || !out) return fail(BDA_EINVAL, "bda_dense_project: NULL device pointer");
+    if (ldc < d_c || ldW < N || ld_out < N) return fail(BDA_EINVAL, "bda_dense_project: leading dimension too small");
+    const size_t esz = dtype_size(dtype), osz = dtype_size(out_dtype);
+    Span so = span_of(out, T, N, ld_out, osz);
+    if (overlaps(so, span_of(c, T, d_c, ldc, esz)) || overlaps(so, span_of(W, d_c, N, ldW, esz)))
+        return fail(BDA_EINVAL, "bda_dense_project: out overlaps an input");
+    GemmArgs a{};
+    a.A = c; a.B = W; a.D = out;
+    a.lda = ldc; a.ldb = ldW; a.ldd = ld_out;
+    a.M = T; a.K = d_c; a.d_h = 0; a.a_skip = 0; a.ident = 0;
+    a.a_off[0] = d_c;
+    int64_t cols[1] = {N};
+    return run_gemm(a, 1, cols, dtype, out_dtype, (hipStream_t)stream);
+}
+
+extern "C" int bda_lowrank_linear(const void* x, int64_t ldx, int64_t T, int d_in, int r, int d_out,
+                                  int basis_offset, const void* Uprime, const void* C, void* out,
+                                  int64_t ld_out, bda_dtype dtype, void* stream)
+{
+    clear_error();
+    if (int rc = check_dtypes("bda_lowrank_linear", dtype, dtype)) return rc;
+    if (T < 0 || d_in <= 0 || r <= 0 || d_out <= r) return fail(BDA_EINVAL, "bda_lowrank_linear: need T >= 0, d_in > 0, 0 < r < d_out");
+    if (basis_offset != 0 && basis_offset != d_out - r) return fail(BDA_EINVAL, "bda_lowrank_linear: basis_offset must be 0 or d_out - r");
+    if (T == 0) return BDA_OK;
+    if (!x || !Uprime || !C || !out) return fail(BDA_EINVAL, "bda_lowrank_linear: NULL device pointer");
+    if (ldx < d_in || ld_out < d_out) return fail(BDA_EINVAL, "bda_lowrank_linear: leading dimension too small");
+    const size_t esz = dtype_size(dtype);
+    const int nc = d_out - r;
+    Span so = span_of(out, T, d_out, ld_out, esz);
+    if (overlaps(so, span_of(x, T, d_in, ldx, esz)) || overlaps(so, span_of(Uprime, d_in, r, r, esz)) ||
+        overlaps(so, span_of(C, r, nc, nc, esz)))
+        return fail(BDA_EINVAL, "bda_lowrank_linear: out overlaps an input");
+    char* ob = (char*)out;
+    void* h_cols = ob + (size_t)basis_offset * esz;                    // where h lives inside out
+    void* c_cols = ob + (size_t)(basis_offset == 0 ? r : 0) * esz;     // where h C goes
+    {   // h = x Uprime
+        GemmArgs a{};
+        a.A = x; a.B = Uprime; a.D = h_cols;
+        a.lda = ldx; a.ldb = r; a.ldd = ld_out;
+        a.M = T; a.K = d_in; a.a_off[0] = d_in;
+        int64_t cols[1] = {r};
+        if (int rc = run_gemm(a, 1, cols, dtype, dtype, (hipStream_t)stream)) return rc;
+    }
+    {   // [.., h C]: reads h back from its columns of out (same stream, so ordered after the first)
+        GemmArgs a{};
+        a.A = h_cols; a.B = C; a.D = c_cols;
+        a.lda = ld_out; a.ldb = nc; a.ldd = ld_out;
+        a.M = T; a.K = r; a.a_off[0] = r;
+        int64_t cols[1] = {nc};
+        return run_gemm(a, 1, cols, dtype, dtype, (hipStream_t)stream);
+    }
+}

@@ -1,0 +1,188 @@
+"""CPU-only tests of libbda: the shared library loads, exports every symbol the header declares,
+its host-side prepare agrees with the oracle, and argument errors are reported, not crashed on.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import bda_workloads as wl
+import oracle
+import paper_2510_01718_amd as bda
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bda.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(bda_[a-z_0-9]+)\s*\(", header))
+    assert {"bda_prepare", "bda_kv_project", "bda_lowrank_linear", "bda_dense_project"} <= declared
+    lib = ctypes.CDLL(bda.lib_path())
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in bda.h but not exported"
+    assert set(bda.exported_symbols()) == declared
+    assert bda.bda_version() >= 100
+
+
+def test_enum_values_match_header():
+    header = open(os.path.join(ROOT, "include", "bda.h")).read()
+    for name, val in [("BDA_F32", bda.BDA_F32), ("BDA_F16", bda.BDA_F16), ("BDA_BF16", bda.BDA_BF16),
+                      ("BDA_F64", bda.BDA_F64), ("BDA_BASIS_FIRST", bda.BASIS_FIRST),
+                      ("BDA_BASIS_LAST", bda.BASIS_LAST), ("BDA_BASIS_RESIDUAL_MIN", bda.BASIS_RESIDUAL_MIN),
+                      ("BDA_BASIS_OFFSET_SEARCH", bda.BASIS_OFFSET_SEARCH), ("BDA_BASIS_EXPLICIT", bda.BASIS_EXPLICIT),
+                      ("BDA_SIDE_NONE", bda.SIDE_NONE), ("BDA_SIDE_Q", bda.SIDE_Q), ("BDA_SIDE_O", bda.SIDE_O)]:
+        m = re.search(rf"\b{name}\s*=\s*(-?\d+)", header)
+        assert m and int(m.group(1)) == val, name
+    # the workload module and the oracle use the same dtype tags (plain data)
+    assert (wl.F32, wl.F16, wl.BF16, wl.F64) == (bda.BDA_F32, bda.BDA_F16, bda.BDA_BF16, bda.BDA_F64)
+    assert (oracle.F32, oracle.F16, oracle.BF16, oracle.F64) == (wl.F32, wl.F16, wl.BF16, wl.F64)
+
+
+@pytest.mark.parametrize("mode", [bda.BASIS_FIRST, bda.BASIS_LAST, bda.BASIS_RESIDUAL_MIN,
+                                  bda.BASIS_OFFSET_SEARCH, bda.BASIS_EXPLICIT])
+@pytest.mark.parametrize("side_kind", [bda.SIDE_NONE, bda.SIDE_Q, bda.SIDE_O])
+@pytest.mark.parametrize("store", [bda.BDA_F16, bda.BDA_BF16, bda.BDA_F32])
+def test_prepare_matches_oracle(mode, side_kind, store):
+    rng = np.random.default_rng(100 + mode * 10 + side_kind)
+    d_c, H, d_h = 80, 3, 16
+    W = rng.standard_normal((d_c, H * d_h)) * 0.1
+    side = None
+    if side_kind == bda.SIDE_Q:
+        side = rng.standard_normal((24, H * d_h))
+    elif side_kind == bda.SIDE_O:
+        side = rng.standard_normal((H * d_h, 40))
+    C, s_out, off, resid = bda.bda_prepare(W, d_c, H, d_h, side, side_kind, mode, 32, store, want_resid=True)
+    Co, so, offo, ro = oracle.prepare(W, d_c, H, d_h, side, side_kind, mode, 32, store)
+    assert off == offo                                        # index selection is exact
+    scale = np.max(np.abs(Co))
+    assert np.max(np.abs(C - Co)) <= 1e-9 * scale
+    if side is not None:
+        assert np.max(np.abs(s_out - so)) <= 1e-10 * np.max(np.abs(so))
+    assert resid[2] == pytest.approx(ro[offo], rel=1e-6)
+    if 0 in ro:
+        assert resid[0] == pytest.approx(ro[0], rel=1e-6)
+    if d_c - d_h in ro:
+        assert resid[1] == pytest.approx(ro[d_c - d_h], rel=1e-6)
+
+
+def test_prepare_tiny_config_basis_rows_identity():
+    w = wl.kv_workload("tiny")
+    C, _, off, _ = bda.bda_prepare(w.W, w.d_c, 2, w.d_h)
+    assert off == 0 and C.shape == (48, 32)
+    for h in range(2):
+        Wh = w.W[:, h * 16:(h + 1) * 16]
+        full = Wh @ np.linalg.inv(Wh[:16])
+        assert np.max(np.abs(full[:16] - np.eye(16))) < 1e-10
+        assert np.max(np.abs(full[16:] - C[:, h * 16:(h + 1) * 16])) < 1e-9
+
+
+def test_prepare_picks_other_window_when_first_is_ill_conditioned():
+    rng = np.random.default_rng(7)
+    d_c, H, d_h = 64, 2, 16
+    W = rng.standard_normal((d_c, H * d_h))
+    for h in range(H):
+        W[1, h * d_h:(h + 1) * d_h] = W[0, h * d_h:(h + 1) * d_h] * (1 + 1e-6)
+    _, _, off, resid = bda.bda_prepare(W, d_c, H, d_h, mode=bda.BASIS_RESIDUAL_MIN, store_dtype=bda.BDA_F16, want_resid=True)
+    _, _, offo, _ = oracle.prepare(W, d_c, H, d_h, mode=oracle.RESIDUAL_MIN, store_dtype=oracle.F16)
+    assert off == offo == d_c - d_h
+    assert resid[0] > resid[1]
+
+
+def test_prepare_tie_keeps_first():
+    d_c, d_h = 10, 3
+    W = np.vstack([np.eye(d_h), np.arange(12, dtype=np.float64).reshape(4, 3), np.eye(d_h)])
+    _, _, off, resid = bda.bda_prepare(W, d_c, 1, d_h, mode=bda.BASIS_RESIDUAL_MIN, store_dtype=bda.BDA_F64, want_resid=True)
+    assert off == 0 and resid[0] == resid[1]
+
+
+def test_prepare_singular_and_invalid():
+    with pytest.raises(bda.BdaError) as e:
+        bda.bda_prepare(np.zeros((8, 4)), 8, 1, 4)
+    assert e.value.status == -4 and "head 0" in e.value.message
+    W = np.ones((8, 4))
+    W[:4] = np.eye(4)
+    W[1] = W[0]                                    # two equal basis rows in the first window
+    with pytest.raises(bda.BdaError) as e:
+        bda.bda_prepare(W, 8, 1, 4)
+    assert e.value.status == -4
+    with pytest.raises(bda.BdaError) as e:
+        bda.bda_prepare(np.ones((8, 4)), 8, 1, 8)          # d_h >= d_c
+    assert e.value.status == -1
+    with pytest.raises(bda.BdaError) as e:
+        bda.bda_prepare(np.ones((8, 4)), 8, 1, 4, mode=bda.BASIS_EXPLICIT, explicit_offset=5)
+    assert e.value.status == -1
+    # residual-min skips a singular window instead of failing
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((12, 4))
+    W[1] = W[0]
+    _, _, off, _ = bda.bda_prepare(W, 12, 1, 4, mode=bda.BASIS_RESIDUAL_MIN)
+    assert off == 8
+
+
+@pytest.mark.parametrize("mode", [bda.BASIS_FIRST, bda.BASIS_LAST, bda.BASIS_RESIDUAL_MIN])
+def test_prepare_lowrank_matches_oracle(mode):
+    rng = np.random.default_rng(21)
+    d_in, r, d_out = 40, 8, 29
+    U = rng.standard_normal((d_in, r))
+    V = rng.standard_normal((r, d_out))
+    Up, C, off, resid = bda.bda_prepare_lowrank(U, V, mode, bda.BDA_F16, want_resid=True)
+    Upo, Co, offo, ro = oracle.prepare_lowrank(U, V, mode, oracle.F16)
+    assert off == offo
+    assert np.max(np.abs(Up - Upo)) <= 1e-11 * np.max(np.abs(Upo))
+    assert np.max(np.abs(C - Co)) <= 1e-9 * np.max(np.abs(Co))
+    if mode == bda.BASIS_RESIDUAL_MIN:
+        assert resid[2] == pytest.approx(ro[offo], rel=1e-6)
+
+
+def test_device_entry_points_reject_bad_arguments_without_a_gpu():
+    """Validation happens before any HIP call, so these return an error code on a CPU-only box."""
+    lib = bda.load()
+    H = (ctypes.c_int * 1)(2)
+    off = (ctypes.c_int * 1)(0)
+    bad_off = (ctypes.c_int * 1)(49)
+    fake = ctypes.c_void_p(0x1000)
+    # d_h >= d_c
+    assert lib.bda_kv_project(fake, 64, 4, 64, 64, 1, H, off, fake, 32, fake, 32, 1, 1, None) == -1
+    # offset out of range
+    assert lib.bda_kv_project(fake, 64, 4, 64, 16, 1, H, bad_off, fake, 32, fake, 32, 1, 1, None) == -1
+    assert b"basis_offset" in lib.bda_last_error()
+    # out_dtype neither dtype nor f32
+    assert lib.bda_kv_project(fake, 64, 4, 64, 16, 1, H, off, fake, 32, fake, 32, 1, 2, None) == -3
+    # too many groups
+    assert lib.bda_kv_project(fake, 64, 4, 64, 16, 9, H, off, fake, 32, fake, 32, 1, 1, None) == -1
+    # ld too small
+    assert lib.bda_kv_project(fake, 8, 4, 64, 16, 1, H, off, fake, 32, fake, 32, 1, 1, None) == -1
+    # NULL pointer with T > 0
+    assert lib.bda_kv_project(None, 64, 4, 64, 16, 1, H, off, fake, 32, fake, 32, 1, 1, None) == -1
+    # out overlapping c
+    assert lib.bda_kv_project(fake, 64, 4, 64, 16, 1, H, off, ctypes.c_void_p(0x100000), 32, fake, 32, 1, 1, None) == -1
+    assert b"overlap" in lib.bda_last_error()
+    # T = 0 is a successful no-op even with NULL buffers
+    assert lib.bda_kv_project(None, 64, 0, 64, 16, 1, H, off, None, 32, None, 32, 1, 1, None) == 0
+    assert lib.bda_last_error() == b""
+    assert lib.bda_dense_project(fake, 64, 4, 64, fake, 8, 32, fake, 32, 1, 1, None) == -1
+    assert lib.bda_lowrank_linear(fake, 64, 4, 64, 8, 40, 3, fake, fake, fake, 40, 1, None) == -1
+    assert lib.bda_set_tile_policy(7) == -1
+    assert lib.bda_set_tile_policy(0) >= 0
+
+
+def test_workload_recipe_is_stable():
+    """The seeded generator is part of the test contract: same seed -> same bits."""
+    a = wl.kv_workload("tiny")
+    b = wl.kv_workload("tiny")
+    assert np.array_equal(a.c_stored, b.c_stored) and np.array_equal(a.W, b.W)
+    assert a.c_stored.dtype == np.float32 and a.c.shape == (64, 64) and a.W.shape == (64, 32)
+    d8 = wl.kv_workload("decode", T=8)
+    d1 = wl.kv_workload("decode", T=1)
+    assert np.array_equal(d8.W, d1.W)                       # weights do not depend on T
+    v = wl.kv_workload("v2lite", T=16)
+    assert np.array_equal(v.W, d8.W)
+    rms = np.sqrt(np.mean(from64(v.c) ** 2, axis=1))
+    assert np.allclose(rms, 1.0, atol=2e-3)
+
+
+def from64(x):
+    return np.asarray(x, dtype=np.float64)
