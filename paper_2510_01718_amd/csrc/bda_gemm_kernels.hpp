@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs p)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lives in an SGPR
     const int wt = wave >> 1, wn = wave & 1;
     const int l31 = lane & 31, lhi = lane >> 5;
 
@@ -342,10 +342,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs p)
                     if (wn * (32 * TN) + c0 >= cols_left) continue;
                     const uint32_t off = row_off + (uint32_t)c0 * (uint32_t)sizeof(OutT);
                     if constexpr (sizeof(OutT) == 4) {
-                        u32x4 v;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = __builtin_bit_cast(uint32_t, acc[ni][ti][rg * 4 + e]);
-                        __builtin_amdgcn_raw_buffer_store_b128(v, rD, off, 0, 0);
+                        // (the elements are copied to named floats first: bit-casting a vector
+                        // element expression directly reads element 0 with this compiler)
+                        const float e0 = acc[ni][ti][rg * 4 + 0], e1 = acc[ni][ti][rg * 4 + 1];
+                        const float e2 = acc[ni][ti][rg * 4 + 2], e3 = acc[ni][ti][rg * 4 + 3];
+                        const f32x4 vf = {e0, e1, e2, e3};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, off, 0, 0);
                     } else {
                         u32x2 v;
                         v[0] = (uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 0]) |
