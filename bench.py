@@ -206,7 +206,7 @@ def main() -> int:
             cd = dev(wl.kv_workload("decode", T=Td).c_stored, w.dtype)
             od = torch.empty((Td, N), dtype=tdt[w.dtype], device="cuda")
             t_d = bench_small(lambda i, s: bda.bda_kv_project(cd, d_c, Td, d_c, d_h, H, offs, C_rot[i % n_w], N,
-                                                              od, N, w.dtype, w.dtype, s), 480, 96)
+                                                              od, N, w.dtype, w.dtype, s), max(8, min(480, args.steps * 2)), max(2, min(96, args.warmup * 2)))
             by = (Td * d_c + K * N + Td * N) * 2.0
             dec[f"T{Td}"] = {"us": t_d * 1e6, "gbs": by / t_d / 1e9, "frac_hbm": by / t_d / 1e9 / HBM_PEAK_GBS}
             log(f"decode T={Td}: {t_d * 1e6:.2f} us, {by / t_d / 1e9:.0f} GB/s")
@@ -219,7 +219,7 @@ def main() -> int:
         C4 = dev(wl.to_storage(rng.standard_normal((K, N4)) * 2.0, wl.BF16)[0], wl.BF16)
         o4 = [torch.empty((T4, N4), dtype=torch.int16, device="cuda") for _ in range(2)]
         t4 = bench_small(lambda i, s: bda.bda_kv_project(c4, d_c, T4, d_c, d_h, [128, 128], [0, 0], C4, N4,
-                                                         o4[i % 2], N4, wl.BF16, wl.BF16, s), 40, 5)
+                                                         o4[i % 2], N4, wl.BF16, wl.BF16, s), max(3, args.steps // 10), max(1, args.warmup // 10))
         f4 = 2.0 * T4 * K * N4
         b4 = (T4 * d_c + K * N4 + T4 * N4) * 2.0
         extra["v3_kv_T8192_bf16"] = {"us": t4 * 1e6, "tflops": f4 / t4 / 1e12, "frac_mfma": f4 / t4 / 1e12 / MFMA_PEAK_TFLOPS,
@@ -228,7 +228,7 @@ def main() -> int:
         log(f"v3: {t4 * 1e6:.1f} us, {f4 / t4 / 1e12:.0f} TFLOP/s, {b4 / t4 / 1e9:.0f} GB/s")
         W4 = dev(wl.to_storage(rng.standard_normal((d_c, N4)) * 0.02, wl.BF16)[0], wl.BF16)
         t4d = bench_small(lambda i, s: bda.bda_dense_project(c4, d_c, T4, d_c, W4, N4, N4, o4[i % 2], N4,
-                                                             wl.BF16, wl.BF16, s), 40, 5)
+                                                             wl.BF16, wl.BF16, s), max(3, args.steps // 10), max(1, args.warmup // 10))
         extra["v3_dense_T8192_bf16"] = {"us": t4d * 1e6, "tflops": 2.0 * T4 * d_c * N4 / t4d / 1e12}
         extra["v3_speedup_vs_dense"] = {"measured": t4d / t4, "theoretical": d_c / K}
         del c4, C4, o4, W4
@@ -239,7 +239,7 @@ def main() -> int:
         C5 = (torch.randn((r5, d_out - r5), device="cuda") * 0.03).to(torch.float16)
         o5 = torch.empty((T5, d_out), dtype=torch.float16, device="cuda")
         t5 = bench_small(lambda i, s: bda.bda_lowrank_linear(x5, d_in, T5, d_in, r5, d_out, 0, U5, C5, o5, d_out,
-                                                             wl.F16, s), 20, 3)
+                                                             wl.F16, s), max(3, args.steps // 20), max(1, args.warmup // 20))
         f5 = 2.0 * T5 * (d_in * r5 + r5 * (d_out - r5))
         extra["lowrank_linear_T8192_f16"] = {"us": t5 * 1e6, "tflops": f5 / t5 / 1e12,
                                              "frac_mfma": f5 / t5 / 1e12 / MFMA_PEAK_TFLOPS, "tokens_per_s": T5 / t5}
@@ -251,7 +251,7 @@ def main() -> int:
         def lowrank_plain(i, s):
             bda.bda_dense_project(x5, d_in, T5, d_in, U5, r5, r5, h5, r5, wl.F16, wl.F16, s)
             bda.bda_dense_project(h5, r5, T5, r5, V5, d_out, d_out, o5, d_out, wl.F16, wl.F16, s)
-        t5p = bench_small(lowrank_plain, 20, 3)
+        t5p = bench_small(lowrank_plain, max(3, args.steps // 20), max(1, args.warmup // 20))
         extra["lowrank_plain_T8192_f16"] = {"us": t5p * 1e6}
         extra["lowrank_speedup_vs_plain"] = {"measured": t5p / t5, "theoretical": (d_in + d_out) / (d_in + d_out - r5)}
         del x5, U5, C5, o5, V5, h5
