@@ -5,6 +5,7 @@
 #include <mutex>
 
 #include "bda_gemm_kernels.hpp"
+#include "bda_gemm_stream.hpp"
 #include "bda_internal.h"
 
 namespace bda {
@@ -46,6 +47,21 @@ int launch_mfma(GemmArgs& a, hipStream_t st)
     auto kern = gemm_mfma_kernel<X, OutT, TT, TN>;
     if (int rc = set_max_lds(kern, lds, once)) return rc;
     hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(256), lds, st, a);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
+// Streaming kernel: 8 waves, stages of 64, two LDS stages (+ 4 KiB of epilogue staging per wave).
+constexpr int kStreamSK = 64, kStreamNS = 2;
+
+template <typename X, typename OutT>
+int launch_stream(GemmArgs& a, hipStream_t st)
+{
+    static std::once_flag once;
+    constexpr int lds = kStreamNS * (256 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
+    auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS, 0>;
+    if (int rc = set_max_lds(kern, lds, once)) return rc;
+    hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
@@ -113,12 +129,16 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         if (big) {
             build_tiles(a, G, group_cols, 256, 256);
             choose_super(a, kSlotsPerXcd);
+            // identity slice: stages of the streaming kernel (the slice of a 256-column tile is the
+            // whole window, or the tile's own 256 columns of it when d_h is a multiple of 256)
+            a.n_stage_id = a.ident ? (((a.d_h % 256) == 0 ? 256 : a.d_h) + kStreamSK - 1) / kStreamSK : 0;
         } else {
             build_tiles(a, G, group_cols, 128, 128);
             choose_super(a, 2 * kSlotsPerXcd);
         }
+        const bool stream = big && (a.K + kStreamSK - 1) / kStreamSK + a.n_stage_id >= kStreamNS;
 #define BDA_LAUNCH(X, O)                                      \
-    return big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
+    return stream ? launch_stream<X, O>(a, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
         if (dtype == BDA_F16 && out_dtype == BDA_F16) { BDA_LAUNCH(F16, uint16_t); }
         if (dtype == BDA_F16 && out_dtype == BDA_F32) { BDA_LAUNCH(F16, float); }
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) { BDA_LAUNCH(BF16, uint16_t); }

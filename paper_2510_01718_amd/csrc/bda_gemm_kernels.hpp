@@ -37,6 +37,7 @@ struct GemmArgs {
     int ident;                       // 1: D starts from A[t, a_off_g + (n - col_start_g) % d_h]
     int m_tiles, n_tiles;            // tile grid (n_tiles counts the tiles of all groups)
     int sm, sn;                      // super-tile shape handed to one die at a time (sm*sn = 32)
+    int n_stage_id;                  // streaming kernel: identity stages per tile (0 if ident == 0)
     int tile_start[kMaxGroups + 1];  // first column tile of each group
     int64_t col_start[kMaxGroups + 1];  // first output column of each group
     int a_off[kMaxGroups];           // basis window start of each group (k >= a_off -> k + a_skip)

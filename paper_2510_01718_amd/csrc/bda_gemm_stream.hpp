@@ -10,7 +10,10 @@
 //   * The contraction is cut into stages of 32 and the LDS holds four stages.  Loads run three
 //     stages ahead of the MFMAs, and the stage sequence continues across output tiles: while the
 //     last stages of one tile are multiplied and its results are stored, the first stages of the
-//     workgroup's next tile are already in flight.  One barrier per stage.
+//     workgroup's next tile are already in flight.  One barrier per stage.  Every workgroup runs
+//     the same number of tiles of the same number of stages (a tile position that falls outside
+//     the grid becomes a tile whose loads fetch nothing and whose stores are dropped), so the
+//     per-stage code has no tile bookkeeping in it.
 //   * Bank conflicts are avoided by permuting which 16-byte piece each lane of a load fetches (the
 //     LDS image of one load instruction is always lane-linear), so the tiles need no padding.
 //   * 16-bit results are exchanged between the two half-waves (v_permlane32_swap) so that every
@@ -21,13 +24,16 @@
 // tracked by hand with s_waitcnt vmcnt(n); every wave issues the same number of loads per stage
 // (loads that have nothing to fetch use an out-of-range offset and return zeros).
 #pragma once
+#include <type_traits>
+
 #include "bda_gemm_kernels.hpp"
 
 namespace bda {
 
-constexpr int kStageK = 32;          // contraction length of one stage
-constexpr int kStages = 4;           // LDS stages
-constexpr int kAhead = kStages - 1;  // stages in flight ahead of the MFMAs
+
+// Cache policy of the result stores: bit 1 = non-temporal.  The output is written once and not read
+// again by this kernel; streaming it keeps the latent and weight tiles in the L2.
+constexpr int kStreamStoreAux = 2;
 
 // s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt = [15:14|3:0]).
 template <int N>
@@ -37,29 +43,29 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// Four LDS DMA loads of 16 bytes per lane through one descriptor; the LDS image of load j starts at
-// lds_base + 1024 j and is lane-linear (lane l -> bytes [16 l, 16 l + 16)).  The LDS address of such a
-// load is M0 + instruction offset + 16 lane, and the instruction offset would also be added to the
-// global address, so M0 is advanced instead.
-__device__ __forceinline__ void lds_dma4(u32x4 rsrc, uint32_t lds_base, uint32_t v0, uint32_t v1,
-                                         uint32_t v2, uint32_t v3)
+// N (2 or 4) LDS DMA loads of 16 bytes per lane through one descriptor; the LDS image of load j
+// starts at lds_base + 1024 j and is lane-linear (lane l -> bytes [16 l, 16 l + 16)).  The LDS address
+// of such a load is M0 + instruction offset + 16 lane, and the instruction offset would also be added
+// to the global address, so M0 is advanced instead.
+__device__ __forceinline__ void lds_dma2(u32x4 rsrc, uint32_t lds_base, uint32_t v0, uint32_t v1)
 {
     asm volatile(
         "s_mov_b32 m0, %0\n\t"
         "s_nop 0\n\t"
-        "buffer_load_dwordx4 %1, %5, 0 offen lds\n\t"
+        "buffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
         "s_add_u32 m0, m0, 0x400\n\t"
         "s_nop 0\n\t"
-        "buffer_load_dwordx4 %2, %5, 0 offen lds\n\t"
-        "s_add_u32 m0, m0, 0x400\n\t"
-        "s_nop 0\n\t"
-        "buffer_load_dwordx4 %3, %5, 0 offen lds\n\t"
-        "s_add_u32 m0, m0, 0x400\n\t"
-        "s_nop 0\n\t"
-        "buffer_load_dwordx4 %4, %5, 0 offen lds\n\t"
+        "buffer_load_dwordx4 %2, %3, 0 offen lds\n\t"
         :
-        : "s"(lds_base), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(rsrc)
+        : "s"(lds_base), "v"(v0), "v"(v1), "s"(rsrc)
         : "memory", "m0", "scc");
+}
+template <int N>
+__device__ __forceinline__ void lds_dma(u32x4 rsrc, uint32_t lds_base, const uint32_t (&v)[N])
+{
+    static_assert(N % 2 == 0, "an even number of loads per call");
+#pragma unroll
+    for (int j = 0; j < N; j += 2) lds_dma2(rsrc, lds_base + 1024u * j, v[j], v[j + 1]);
 }
 
 __device__ __forceinline__ u32x4 make_rsrc_words(const void* base, int64_t bytes)
@@ -74,81 +80,108 @@ __device__ __forceinline__ u32x4 make_rsrc_words(const void* base, int64_t bytes
     return r;
 }
 
-// Token tile in LDS: row = 32 k = 64 bytes = four 16-byte pieces; piece q of row r sits at position
-// q ^ tok_swz(r).  Chosen so that the 32 lanes of a fragment read (32 consecutive rows, same q) are
-// conflict-free whether the LDS serves 16 lanes x 16 bytes over 64 banks or 8 lanes over 32 banks.
-__device__ __forceinline__ int tok_swz(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
+// Token tile in LDS: row = SK k = four (SK = 32) or eight (SK = 64) 16-byte pieces; piece q of row r
+// sits at position q ^ tok_swz<SK>(r).  Chosen so that the 32 lanes of a fragment read (32
+// consecutive rows, same q) are conflict-free whether the LDS serves 16 lanes x 16 bytes over 64
+// banks or 8 lanes over 32 banks.
+template <int SK>
+__device__ __forceinline__ int tok_swz(int r)
+{
+    if constexpr (SK == 32)
+        return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1);
+    else
+        return (r ^ (r >> 3)) & 7;
+}
 // Weight tile in LDS: row = one k = 256 columns = 512 bytes = thirty-two 16-byte pieces; piece c of
 // row k sits at position c ^ wgt_swz(k): the four rows one transposing read touches spread over
 // different banks.
 __device__ __forceinline__ int wgt_swz(int k) { return (k & 3) * 5; }
 
-struct TileInfo {
-    int valid;
-    int super;                 // super-tile index this tile came from (the iterator's position)
-    int mt;                    // token tile
-    int rel0;                  // first column of the tile inside its group
-    int64_t n0;                // first output column of the tile
-    int cols_left;             // valid columns of the tile (a group may end inside it)
+struct StreamTile {
+    u32x4 rA, rB;              // producer descriptors (range 0 for a tile outside the grid)
+    int64_t d_off;             // element offset of the tile's first output
+    int64_t rows_left;         // valid token rows from the tile's first row (<= 0: none)
+    int cols_left;             // valid columns of the tile (a group may end inside it; 0: none)
     int a_off;                 // basis window start of the tile's group
-    int j_lo, n_id, n_stage;   // identity slice start, identity stages, total stages
+    int rel0;                  // first column of the tile inside its group
+    int j_lo;                  // first identity-slice column the tile needs
 };
 
 // DBG is for timing experiments only (0 in the library): bit 0 drops the result stores, bit 1 the
 // MFMAs, bit 2 the global loads.
-template <typename X, typename OutT, int DBG = 0>
-__global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p)
+//
+// WT x WN waves share the 256 x 256 tile: 2 x 2 waves of 128 x 128 (one wave per SIMD) or 2 x 4 waves
+// of 128 tokens x 64 columns (two waves per SIMD, so that one wave's LDS reads, barrier wait and
+// address arithmetic overlap the other's MFMAs).
+//
+// SK = contraction length of one stage (32 or 64), NS = LDS stages (a power of two); loads run
+// NS - 1 stages ahead of the MFMAs.
+//
+// Host contract: p.n_stage_id = identity stages per tile (the same for every tile of a launch),
+// stages per tile S = ceil(K / SK) + n_stage_id >= NS; grid = 8 * sm * sn workgroups;
+// dynamic LDS = NS * (256 * 2 SK + SK * 512) + 4096 * waves.
+template <typename X, typename OutT, int WT, int WN, int SK, int NS, int DBG = 0>
+__global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArgs p)
 {
-    constexpr int TT = 4, TN = 4;
+    constexpr int kStageK = SK, kStages = NS, kAhead = NS - 1;
+    constexpr int NW = WT * WN;
+    constexpr int TT = 8 / WT, TN = 8 / WN;
     constexpr int BT = 256, BN = 256;
-    constexpr int TOK_BYTES = BT * 64;                 // 16 KiB
-    constexpr int STAGE_BYTES = TOK_BYTES + kStageK * BN * 2;   // 32 KiB
-    constexpr int LOADS = 8;                           // per thread per stage: 4 token + 4 weight
-    constexpr int STORES = sizeof(OutT) == 4 ? 64 : 32;   // 16-byte stores per thread per tile
+    constexpr int PR = SK / 8;                         // 16-byte pieces per token row
+    constexpr int RB = SK * 2;                         // bytes per token row in LDS
+    constexpr int RPI = 64 / PR;                       // token rows per load instruction
+    constexpr int KS = SK / 16;                        // k-steps per stage
+    constexpr int PIT = BT / RPI / NW;                 // token load instructions per wave per stage
+    constexpr int PIW = SK / 2 / NW;                   // weight load instructions per wave per stage
+    constexpr int TOK_BYTES = BT * RB;
+    constexpr int STAGE_BYTES = TOK_BYTES + SK * BN * 2;
+    constexpr int LOADS = PIT + PIW;                   // per thread per stage
+    constexpr int STORES = TT * TN * (sizeof(OutT) == 4 ? 4 : 2);   // 16-byte stores per thread per tile
+    constexpr int WAIT_STEADY = (NS - 2) * LOADS;      // the younger stages may stay in flight
+    constexpr int WAIT_AFTER_STORES = WAIT_STEADY + STORES < 63 ? WAIT_STEADY + STORES : 63;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wt = wave >> 1, wn = wave & 1;
+    const int wt = wave / WN, wn = wave % WN;
     const int l31 = lane & 31, lhi = lane >> 5;
 
     const int nk = (p.K + kStageK - 1) / kStageK;
+    const int n_id = p.ident ? p.n_stage_id : 0;
+    const int S = nk + n_id;
     const int n_super_n = (p.n_tiles + p.sn - 1) / p.sn;
     const int n_super_m = (p.m_tiles + p.sm - 1) / p.sm;
     const int total_super = n_super_m * n_super_n;
-    const int slots = p.sm * p.sn;
+    const int n_rounds = (total_super + kNumXcd - 1) / kNumXcd;
     const int xcd = blockIdx.x % kNumXcd;
     const int slot = blockIdx.x / kNumXcd;
-    if (slot >= slots) return;
+    const int slot_m = slot / p.sn, slot_n = slot % p.sn;
 
-    // ---- tile iterator ---------------------------------------------------------------------
-    auto tile_at = [&](int s) -> TileInfo {
-        TileInfo ti{};
-        for (; s < total_super; s += kNumXcd) {
-            const int mt = (s / n_super_n) * p.sm + slot / p.sn;
-            const int nt = (s % n_super_n) * p.sn + slot % p.sn;
-            if (mt < p.m_tiles && nt < p.n_tiles) {
-                int g = 0;
-                while (g + 1 < p.n_groups && nt >= p.tile_start[g + 1]) ++g;
-                ti.valid = 1;
-                ti.super = s;
-                ti.mt = mt;
-                ti.rel0 = (nt - p.tile_start[g]) * BN;
-                ti.n0 = p.col_start[g] + ti.rel0;
-                const int64_t left = p.col_start[g + 1] - ti.n0;
-                ti.cols_left = (int)(left > BN ? BN : left);
-                ti.a_off = p.a_off[g];
-                if (p.ident) {
-                    const bool nested = (p.d_h % BN) == 0;
-                    ti.j_lo = nested ? ti.rel0 % p.d_h : 0;
-                    ti.n_id = ((nested ? BN : p.d_h) + kStageK - 1) / kStageK;
-                }
-                ti.n_stage = nk + ti.n_id;
-                return ti;
-            }
-        }
-        return ti;
+    // ---- tile set-up (scalar; once per tile) ------------------------------------------------------
+    auto setup = [&](int round) -> StreamTile {
+        StreamTile t;
+        const int sidx = round * kNumXcd + xcd;
+        const int mt = (sidx / n_super_n) * p.sm + slot_m;
+        const int nt = (sidx % n_super_n) * p.sn + slot_n;
+        const bool valid = round < n_rounds && sidx < total_super && mt < p.m_tiles && nt < p.n_tiles;
+        int g = 0;
+        while (g + 1 < p.n_groups && nt >= p.tile_start[g + 1]) ++g;
+        const int rel0 = valid ? (nt - p.tile_start[g]) * BN : 0;
+        const int64_t n0 = valid ? p.col_start[g] + rel0 : 0;
+        const int64_t left = p.col_start[g + 1] - n0;
+        const int64_t t0 = valid ? (int64_t)mt * BT : 0;
+        t.rows_left = valid ? p.M - t0 : 0;
+        t.cols_left = valid ? (int)(left > BN ? BN : left) : 0;
+        t.a_off = p.a_off[g];
+        t.rel0 = rel0;
+        t.j_lo = (p.ident && (p.d_h % BN) == 0) ? rel0 % p.d_h : 0;
+        t.d_off = t0 * p.ldd + n0;
+        t.rA = make_rsrc_words((const char*)p.A + t0 * p.lda * 2,
+                               valid ? ((t.rows_left - 1) * p.lda + p.K + p.a_skip) * 2 : 0);
+        t.rB = make_rsrc_words((const char*)p.B + n0 * 2,
+                               valid ? ((int64_t)(p.K - 1) * p.ldb + t.cols_left) * 2 : 0);
+        return t;
     };
 
     // ---- per-lane constants ------------------------------------------------------------------
@@ -162,97 +195,75 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p)
             idf[v][w] = (k0 == l31 ? IdentityFrag<X>::one : 0u) | (k0 + 1 == l31 ? IdentityFrag<X>::one << 16 : 0u);
         }
 
-    // producer, token tile: load j of wave w fills LDS rows w*64 + 16 j + lane/4, position lane%4
-    const int p_tok_row = wave * 64 + (lane >> 2);
-    const int p_tok_q = (lane & 3) ^ tok_swz(lane >> 2);          // rows differ by multiples of 16
+    // producer, token tile: load j of wave w fills LDS rows RPI (w PIT + j) + lane/PR, position lane%PR
     const uint32_t tok_row_bytes = (uint32_t)(p.lda * 2);
-    // producer, weight tile: load j of wave w fills k rows w*8 + 2 j + lane/32, position lane%32
-    const int p_wgt_k = wave * 8 + (lane >> 5);
+    const uint32_t p_tok_row_off = (uint32_t)(wave * (RPI * PIT) + lane / PR) * tok_row_bytes;
+    // column of this lane's piece inside the stage; the swizzle sees row bits 0..3, of which bit 3
+    // alternates with j when a load covers only 8 rows
+    int p_tok_k8[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) p_tok_k8[j] = ((lane % PR) ^ tok_swz<SK>((lane / PR + RPI * j) & 15)) * 8;
+    // producer, weight tile: load j of wave w fills k rows 2 (w PIW + j) + lane/32, position lane%32
     const uint32_t wgt_row_bytes = (uint32_t)(p.ldb * 2);
-    int p_wgt_c[4];
+    const uint32_t p_wgt_row_off = (uint32_t)(wave * (2 * PIW) + (lane >> 5)) * wgt_row_bytes;
+    int p_wgt_c[2];                                   // the swizzle sees k & 3 = (2 j + lane/32) & 3
 #pragma unroll
-    for (int j = 0; j < 4; ++j) p_wgt_c[j] = (lane & 31) ^ wgt_swz(2 * j + (lane >> 5));
+    for (int j = 0; j < 2; ++j) p_wgt_c[j] = (lane & 31) ^ wgt_swz(2 * j + (lane >> 5));
+    static_assert((RPI * PIT) % 16 == 0 && (2 * PIW) % 4 == 0, "per-wave row blocks must keep the swizzle phase");
 
-    // consumer, token fragments: row = wt*128 + ti*32 + l31, piece q = 2 ks + lhi
-    uint32_t c_tok[2];
+    // consumer, token fragments: row = wt*32*TT + ti*32 + l31, piece q = 2 ks + lhi
+    uint32_t c_tok[KS];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-        c_tok[ks] = (uint32_t)((wt * 128 + l31) * 64 + (((2 * ks + lhi) ^ tok_swz(l31)) << 4));
+    for (int ks = 0; ks < KS; ++ks)
+        c_tok[ks] = (uint32_t)((wt * (32 * TT) + l31) * RB + (((2 * ks + lhi) ^ tok_swz<SK>(l31 & 15)) << 4));
     // consumer, weight fragments (transposing read): 16-lane group gq = lane/16, s = lane%16:
-    // k = 16 ks + 8 lhi + 4 rd + s/4, columns wn*128 + ni*32 + 16 (gq&1) + 4 (s&3) .. +3
+    // k = 16 ks + 8 lhi + 4 rd + s/4, columns wn*32*TN + ni*32 + 16 (gq&1) + 4 (s&3) .. +3
     const int c_s = lane & 15, c_gq = lane >> 4;
     uint32_t c_wgt[TN];
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni) {
-        const int col = wn * 128 + ni * 32 + 16 * (c_gq & 1) + 4 * (c_s & 3);
+        const int col = wn * (32 * TN) + ni * 32 + 16 * (c_gq & 1) + 4 * (c_s & 3);
         const int piece = (col >> 3) ^ wgt_swz(c_s >> 2);
         c_wgt[ni] = (uint32_t)(TOK_BYTES + (8 * lhi + (c_s >> 2)) * 512 + (piece << 4) + ((col & 4) << 1));
     }
 
-    // ---- producer -------------------------------------------------------------------------------
-    TileInfo pt = tile_at(xcd);
-    int pk = 0;            // next stage of pt to load
-    int pcount = 0;        // stages issued so far (LDS slot = pcount % kStages)
-    u32x4 rA = {0, 0, 0, 0}, rB = {0, 0, 0, 0};
-    auto producer_enter_tile = [&]() {
-        if (pt.valid) {
-            const int64_t t0 = (int64_t)pt.mt * BT;
-            const int64_t rows_left = p.M - t0;
-            rA = make_rsrc_words((const char*)p.A + t0 * p.lda * 2, ((rows_left - 1) * p.lda + p.K + p.a_skip) * 2);
-            rB = make_rsrc_words((const char*)p.B + pt.n0 * 2, ((int64_t)(p.K - 1) * p.ldb + pt.cols_left) * 2);
-        }
-    };
-    producer_enter_tile();
-    auto produce = [&]() {
-        // always issues LOADS loads per thread (out-of-range ones return zeros) while a tile is left
-        const uint32_t lds_slot = (uint32_t)((pcount % kStages) * STAGE_BYTES);
-        uint32_t tv[4], wv[4];
-        if (pk < nk) {
-            const int k = pk * kStageK + p_tok_q * 8;
-            const int col = k < pt.a_off ? k : k + p.a_skip;
-            const uint32_t base = k < p.K ? (uint32_t)p_tok_row * tok_row_bytes + (uint32_t)col * 2u : kBadOffset;
+    // ---- producer: stage `k` of tile `t` into LDS slot `g & 3` -------------------------------------
+    // Always issues LOADS loads per thread; whatever has nothing to fetch (weights of an identity
+    // stage, columns past the group's end, a tile outside the grid) uses an out-of-range offset.
+    auto produce = [&](const StreamTile& t, int k, int g) {
+        uint32_t tv[PIT], wv[PIW];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) tv[j] = base + (uint32_t)(16 * j) * tok_row_bytes;
-            const uint32_t kbase = (uint32_t)(pk * kStageK + p_wgt_k) * wgt_row_bytes;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                wv[j] = p_wgt_c[j] * 8 < pt.cols_left ? kbase + (uint32_t)(2 * j) * wgt_row_bytes + (uint32_t)p_wgt_c[j] * 16u
-                                                       : kBadOffset;
-        } else {
-            const int jcol = pt.j_lo + (pk - nk) * kStageK + p_tok_q * 8;
-            const uint32_t base = jcol < p.d_h ? (uint32_t)p_tok_row * tok_row_bytes + (uint32_t)(pt.a_off + jcol) * 2u : kBadOffset;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                tv[j] = base + (uint32_t)(16 * j) * tok_row_bytes;
-                wv[j] = kBadOffset;
+        for (int j = 0; j < PIT; ++j) {
+            int col, lim_ok;
+            if (k < nk) {
+                const int kk = k * SK + p_tok_k8[j & 1];
+                col = kk < t.a_off ? kk : kk + p.a_skip;
+                lim_ok = kk < p.K;
+            } else {
+                const int jc = t.j_lo + (k - nk) * SK + p_tok_k8[j & 1];
+                col = t.a_off + jc;
+                lim_ok = jc < p.d_h;
             }
+            tv[j] = lim_ok ? p_tok_row_off + (uint32_t)(RPI * j) * tok_row_bytes + (uint32_t)col * 2u : kBadOffset;
         }
+        const uint32_t wbase = k < nk ? p_wgt_row_off + (uint32_t)(k * SK) * wgt_row_bytes : kBadOffset;
+#pragma unroll
+        for (int j = 0; j < PIW; ++j)
+            wv[j] = p_wgt_c[j & 1] * 8 < t.cols_left ? wbase + (uint32_t)(2 * j) * wgt_row_bytes + (uint32_t)p_wgt_c[j & 1] * 16u
+                                                      : kBadOffset;
         if constexpr (!(DBG & 4)) {
-            lds_dma4(rA, lds_slot + (uint32_t)wave * 4096u, tv[0], tv[1], tv[2], tv[3]);
-            lds_dma4(rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * 4096u, wv[0], wv[1], wv[2], wv[3]);
-        }
-        ++pcount;
-        if (++pk == pt.n_stage) {
-            pt = tile_at(pt.super + kNumXcd);
-            pk = 0;
-            producer_enter_tile();
+            const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
+            lds_dma<PIT>(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT), tv);
+            lds_dma<PIW>(t.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW), wv);
         }
     };
 
-    // prologue: kAhead stages in flight
-    int issued_real = 0;
-#pragma unroll 1
-    for (int i = 0; i < kAhead; ++i) {
-        if (pt.valid) {
-            produce();
-            ++issued_real;
-        }
-    }
-
-    // ---- consumer -------------------------------------------------------------------------------
-    TileInfo ct = tile_at(xcd);
-    int ccount = 0;
-    int since_store = 100;     // stages consumed since the last epilogue (its stores sit in vmcnt too)
+    // ---- consumer ---------------------------------------------------------------------------------
+    // Each stage is two k-steps of 16.  The fragments of a k-step are read from LDS one k-step
+    // before its MFMAs are issued (two register sets), so within a wave the LDS latency, the
+    // barrier, the producer's address arithmetic and the DMA issue sit behind queued MFMAs:
+    //     read(stage i, k-step 1) | MFMA(stage i, k-step 0) | wait + barrier + produce(stage i + 4)
+    //     | read(stage i + 1, k-step 0) | MFMA(stage i, k-step 1) | ...
     auto mm = [](u32x4 a, u32x4 b, f32x16 c) -> f32x16 {
         if constexpr (DBG & 2) {
             c[0] += __builtin_bit_cast(float, a[0] ^ b[0]);     // keeps the operands alive
@@ -265,23 +276,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p)
     const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+    u32x4 fw0[TN], ft0[TT], fw1[TN], ft1[TT];
 
-    // waits until stage `ccount` has landed in LDS for every wave, then refills the slot that has
-    // just been read.  Younger operations may stay in flight: the loads of the stages behind it
-    // and, shortly after an epilogue, that epilogue's stores (they count in vmcnt as well).
-    auto stage_begin = [&]() {
-        if (!pt.valid) {
-            wait_vmcnt<0>();
-        } else if (since_store < kAhead) {
-            wait_vmcnt<(kAhead - 1) * LOADS + STORES < 63 ? (kAhead - 1) * LOADS + STORES : 63>();
-        } else {
-            wait_vmcnt<(kAhead - 1) * LOADS>();
-        }
-        __syncthreads();
-        if (pt.valid) produce();
-        ++since_store;
-    };
-    auto load_frags = [&](uint32_t sbase, int ks, u32x4 (&fw)[TN], u32x4 (&ft)[TT]) {
+    auto read_w = [&](uint32_t sbase, int ks, u32x4 (&fw)[TN]) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + sbase + c_wgt[ni] + (16 * ks) * 512));
@@ -289,77 +286,108 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p)
             const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
             fw[ni] = (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
         }
+    };
+    auto read_t = [&](uint32_t sbase, int ks, u32x4 (&ft)[TT]) {
 #pragma unroll
-        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(smem + sbase + c_tok[ks] + ti * 2048);
+        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(smem + sbase + c_tok[ks] + ti * (32 * RB));
+    };
+    auto mma_regular = [&](const u32x4 (&fw)[TN], const u32x4 (&ft)[TT]) {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw[ni], ft[ti], acc[ni][ti]);
+    };
+    int rel_wave = 0;
+    auto mma_identity = [&](int col0, const u32x4 (&ft)[TT]) {
+        // col0: first of the 16 slice columns this k-step holds
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) {
+            const int d = col0 - (rel_wave + 32 * ni) % p.d_h;
+            if (d == 0 || d == 16) {
+                const u32x4 f = d == 0 ? idf[0] : idf[1];
+#pragma unroll
+                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(f, ft[ti], acc[ni][ti]);
+            }
+        }
+    };
+    auto slot_base = [&](int g) { return (uint32_t)((g & (kStages - 1)) * STAGE_BYTES); };
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = zero16;
     };
 
-    while (ct.valid) {
-        const int rel_wave = (ct.rel0 + wn * (32 * TN)) % (p.d_h > 0 ? p.d_h : 1);
+    // One stage of the consumer's tile `cur` (stage kc, global stage counter g), during which stage
+    // `pk` of tile `pt` is loaded.  `regular`: compile-time kind of the stage (rows of B, or a piece
+    // of the identity slice).  `relaxed`: an epilogue's stores may still be in flight.
+    auto stage = [&](auto regular, const StreamTile& cur, int kc, int g, const StreamTile& pt, int pk, bool relaxed) {
+        constexpr bool REG = decltype(regular)::value;
+        const uint32_t sb = slot_base(g), nb = slot_base(g + 1);
+        const bool next_regular = kc + 1 < nk || kc + 1 == S;
+        const int jc = cur.j_lo + (kc - nk) * SK;
+        // k-steps 0 .. KS-2: read the next k-step's fragments, multiply the current ones
+#pragma unroll
+        for (int ks = 0; ks + 1 < KS; ++ks) {
+            if (ks % 2 == 0) {
+                if constexpr (REG) { read_w(sb, ks + 1, fw1); read_t(sb, ks + 1, ft1); mma_regular(fw0, ft0); }
+                else { read_t(sb, ks + 1, ft1); mma_identity(jc + 16 * ks, ft0); }
+            } else {
+                if constexpr (REG) { read_w(sb, ks + 1, fw0); read_t(sb, ks + 1, ft0); mma_regular(fw1, ft1); }
+                else { read_t(sb, ks + 1, ft0); mma_identity(jc + 16 * ks, ft1); }
+            }
+        }
+        // stage g + 1 must have landed for every wave, and every wave must be done with stage g's
+        // slot (this wave's reads of it are all issued; the barrier's fence completes them)
+        if (relaxed) wait_vmcnt<WAIT_AFTER_STORES>(); else wait_vmcnt<WAIT_STEADY>();
+        __syncthreads();
+        produce(pt, pk, g);                   // stage g + NS goes into the slot just freed
+        if (next_regular) read_w(nb, 0, fw0);
+        read_t(nb, 0, ft0);
+        if constexpr (REG)
+            mma_regular(fw1, ft1);            // KS is even: the last k-step sits in the second set
+        else
+            mma_identity(jc + 16 * (KS - 1), ft1);
+    };
 
-        // first stage of the tile: its first k-step starts the accumulators from zero (the zero is
-        // an operand of the MFMA, no register is cleared)
-        {
-            stage_begin();
-            const uint32_t sbase = (uint32_t)((ccount % kStages) * STAGE_BYTES);
-            u32x4 fw[TN], ft[TT];
-            load_frags(sbase, 0, fw, ft);
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw[ni], ft[ti], zero16);
-            load_frags(sbase, 1, fw, ft);
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw[ni], ft[ti], acc[ni][ti]);
-            ++ccount;
-        }
+    StreamTile cur = setup(0);
+    int g = 0;
+    // prologue: the first kStages stages of the first tile
 #pragma unroll 1
-        for (int kc = 1; kc < nk; ++kc) {
-            stage_begin();
-            const uint32_t sbase = (uint32_t)((ccount % kStages) * STAGE_BYTES);
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                u32x4 fw[TN], ft[TT];
-                load_frags(sbase, ks, fw, ft);
-#pragma unroll
-                for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                    for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw[ni], ft[ti], acc[ni][ti]);
-            }
-            ++ccount;
-        }
+    for (int k = 0; k < kStages; ++k) produce(cur, k, k);
+    clear_acc();
+    wait_vmcnt<(kStages - 1) * LOADS>();
+    __syncthreads();
+    read_w(slot_base(0), 0, fw0);
+    read_t(slot_base(0), 0, ft0);
+
+    const std::true_type REGULAR{};
+    const std::false_type IDENTITY{};
+    const int split = S - kStages;            // from this stage on, the next tile is being loaded
+    const int r_same = nk < split ? nk : split;
+    const int i_same = split > nk ? split : nk;
 #pragma unroll 1
-        for (int kc = nk; kc < ct.n_stage; ++kc) {
-            stage_begin();
-            const uint32_t sbase = (uint32_t)((ccount % kStages) * STAGE_BYTES);
-            const int jc = ct.j_lo + (kc - nk) * kStageK;     // first slice column of this stage
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                u32x4 ft[TT];
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(smem + sbase + c_tok[ks] + ti * 2048);
-#pragma unroll
-                for (int ni = 0; ni < TN; ++ni) {
-                    const int d = jc + 16 * ks - (rel_wave + 32 * ni) % p.d_h;
-                    if (d == 0 || d == 16) {
-                        const u32x4 f = d == 0 ? idf[0] : idf[1];
-#pragma unroll
-                        for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(f, ft[ti], acc[ni][ti]);
-                    }
-                }
-            }
-            ++ccount;
-        }
+    for (int round = 0; round < n_rounds; ++round) {
+        const StreamTile nxt = setup(round + 1);
+        rel_wave = (cur.rel0 + wn * (32 * TN)) % (p.d_h > 0 ? p.d_h : 1);
+        const bool after_tile = round > 0;
+        int kc = 0;
+#pragma unroll 1
+        for (; kc < r_same; ++kc, ++g) stage(REGULAR, cur, kc, g, cur, kc + kStages, after_tile && kc < (kAhead > 1 ? kAhead : 1));
+#pragma unroll 1
+        for (; kc < nk; ++kc, ++g) stage(REGULAR, cur, kc, g, nxt, kc - split, after_tile && kc < (kAhead > 1 ? kAhead : 1));
+#pragma unroll 1
+        for (; kc < i_same; ++kc, ++g) stage(IDENTITY, cur, kc, g, cur, kc + kStages, after_tile && kc < (kAhead > 1 ? kAhead : 1));
+#pragma unroll 1
+        for (; kc < S; ++kc, ++g) stage(IDENTITY, cur, kc, g, nxt, kc - split, after_tile && kc < (kAhead > 1 ? kAhead : 1));
 
         // ---- epilogue ---------------------------------------------------------------------------
-        const int64_t ct0 = (int64_t)ct.mt * BT;
-        const int64_t rows_left = p.M - ct0;
+        // rows past the end of the tensor and tiles outside the grid fall outside rD's range
         const __amdgpu_buffer_rsrc_t rD = make_rsrc(
-            (char*)p.D + (ct0 * p.ldd + ct.n0) * (int64_t)sizeof(OutT),
-            ((rows_left - 1) * p.ldd + ct.cols_left) * (int64_t)sizeof(OutT));
+            (char*)p.D + cur.d_off * (int64_t)sizeof(OutT),
+            cur.cols_left > 0 ? ((cur.rows_left - 1) * p.ldd + cur.cols_left) * (int64_t)sizeof(OutT) : 0);
         const uint32_t ep_row_step = 32u * (uint32_t)(p.ldd * sizeof(OutT));
-        const bool full = ct.cols_left == BN;      // uniform; a group may end inside its last tile
+        const bool full = cur.cols_left == BN;      // uniform; a group may end inside its last tile
         if constexpr (DBG & 1) {
             float sum = 0.f;
 #pragma unroll
@@ -381,53 +409,65 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p)
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg) {
                         const int c0 = ni * 32 + rg * 8;
-                        if (!full && wn * (32 * TN) + c0 >= ct.cols_left) continue;
+                        if (!full && wn * (32 * TN) + c0 >= cur.cols_left) continue;
                         const float e0 = acc[ni][ti][rg * 4 + 0], e1 = acc[ni][ti][rg * 4 + 1];
                         const float e2 = acc[ni][ti][rg * 4 + 2], e3 = acc[ni][ti][rg * 4 + 3];
                         const f32x4 vf = {e0, e1, e2, e3};
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, ep_row, c0 * 4, 0);
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, ep_row, c0 * 4, kStreamStoreAux);
                     }
                 }
             }
         } else {
             // lanes l and l+32 hold columns 0..3 and 4..7 of the same 8-column block; after the swap
             // the lower half-wave owns the even blocks and the upper half-wave the odd blocks, each
-            // lane with 8 consecutive columns = 16 bytes
-            uint32_t ep_row = (uint32_t)(wt * (32 * TT) + l31) * (uint32_t)(p.ldd * 2) + (uint32_t)(wn * (32 * TN) + lhi * 8) * 2u;
+            // lane with 8 consecutive columns = 16 bytes.  A 32-row x 64-column piece is then turned
+            // round in a 4 KiB LDS region private to the wave, so that 8 consecutive lanes store one
+            // full 128-byte line of a row (the memory pipeline works on whole lines).
+            unsigned char* stag = smem + kStages * STAGE_BYTES + wave * 4096;
+            const int st_wr = l31 * 128;                                    // + ((chunk ^ sw) << 4)
+            const int st_sw = (l31 ^ (l31 >> 3)) & 7;
+            const int rd_row = lane >> 3, rd_chunk = lane & 7;
+            uint32_t g_row = (uint32_t)(wt * (32 * TT) + rd_row) * (uint32_t)(p.ldd * 2) + (uint32_t)(wn * (32 * TN) + rd_chunk * 8) * 2u;
+            const uint32_t g_step8 = 8u * (uint32_t)(p.ldd * 2);
 #pragma unroll
             for (int ti = 0; ti < TT; ++ti) {
-                if (ti) ep_row += ep_row_step;
-                asm volatile("" : "+v"(ep_row));    // keeps the offset a per-tile value (one register)
 #pragma unroll
-                for (int ni = 0; ni < TN; ++ni) {
+                for (int h = 0; h < TN / 2; ++h) {
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int pr = 0; pr < 2; ++pr) {
-                        uint32_t xv[2], yv[2];
+                    for (int nn = 0; nn < 2; ++nn) {
+                        const int ni = 2 * h + nn;
 #pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            xv[h] = (uint32_t)X::from_f32(acc[ni][ti][(2 * pr) * 4 + 2 * h]) |
-                                    ((uint32_t)X::from_f32(acc[ni][ti][(2 * pr) * 4 + 2 * h + 1]) << 16);
-                            yv[h] = (uint32_t)X::from_f32(acc[ni][ti][(2 * pr + 1) * 4 + 2 * h]) |
-                                    ((uint32_t)X::from_f32(acc[ni][ti][(2 * pr + 1) * 4 + 2 * h + 1]) << 16);
+                        for (int pr = 0; pr < 2; ++pr) {
+                            uint32_t xv[2], yv[2];
+#pragma unroll
+                            for (int q = 0; q < 2; ++q) {
+                                xv[q] = (uint32_t)X::from_f32(acc[ni][ti][(2 * pr) * 4 + 2 * q]) |
+                                        ((uint32_t)X::from_f32(acc[ni][ti][(2 * pr) * 4 + 2 * q + 1]) << 16);
+                                yv[q] = (uint32_t)X::from_f32(acc[ni][ti][(2 * pr + 1) * 4 + 2 * q]) |
+                                        ((uint32_t)X::from_f32(acc[ni][ti][(2 * pr + 1) * 4 + 2 * q + 1]) << 16);
+                            }
+                            const u32x2 s0 = __builtin_amdgcn_permlane32_swap(xv[0], yv[0], false, false);
+                            const u32x2 s1 = __builtin_amdgcn_permlane32_swap(xv[1], yv[1], false, false);
+                            const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+                            const int chunk = nn * 4 + pr * 2 + lhi;        // 16-byte piece of the 64 columns
+                            *(u32x4*)(stag + st_wr + ((chunk ^ st_sw) << 4)) = v;
                         }
-                        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(xv[0], yv[0], false, false);
-                        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(xv[1], yv[1], false, false);
-                        const int c0 = ni * 32 + pr * 16;           // this pair's two 8-column blocks
-                        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
-                        // the column offset is a compile-time constant: it travels in the
-                        // instruction's scalar-offset operand, not in a register per store
-                        if (full) {
-                            __builtin_amdgcn_raw_buffer_store_b128(v, rD, ep_row, c0 * 2, 0);
-                        } else if (wn * (32 * TN) + c0 + lhi * 8 < ct.cols_left) {
-                            __builtin_amdgcn_raw_buffer_store_b128(v, rD, ep_row, c0 * 2, 0);
-                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int row = j * 8 + rd_row;
+                        const u32x4 v = *(const u32x4*)(stag + row * 128 + ((rd_chunk ^ ((row ^ (row >> 3)) & 7)) << 4));
+                        uint32_t off = g_row + (uint32_t)(ti * 4 + j) * g_step8;
+                        asm volatile("" : "+v"(off));
+                        const bool ok = full || wn * (32 * TN) + h * 64 + rd_chunk * 8 < cur.cols_left;
+                        if (ok) __builtin_amdgcn_raw_buffer_store_b128(v, rD, off, h * 128, kStreamStoreAux);
                     }
                 }
             }
         }
-        since_store = 0;
-        ct = tile_at(ct.super + kNumXcd);
+        clear_acc();
+        cur = nxt;
     }
     wait_vmcnt<0>();
 }
