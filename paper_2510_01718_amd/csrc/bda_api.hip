@@ -5,6 +5,7 @@
 #include <mutex>
 
 #include "bda_gemm_kernels.hpp"
+#include "bda_decode.hpp"
 #include "bda_gemm_stream.hpp"
 #include "bda_internal.h"
 
@@ -66,6 +67,19 @@ int launch_stream(GemmArgs& a, hipStream_t st)
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
 
+template <typename X, typename OutT>
+int launch_decode(GemmArgs& a, hipStream_t st)
+{
+    static std::once_flag once;
+    auto kern = kv_decode_kernel<X, OutT>;
+    if (int rc = set_max_lds(kern, kDecodeMaxK * 64 + 32768, once)) return rc;
+    const int lds = ((a.K + 15) / 16) * 1024 + 32768;
+    const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
+    hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
 template <typename InT, typename OutT>
 int launch_general(GemmArgs& a, int64_t N_total, hipStream_t st)
 {
@@ -112,13 +126,23 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     const size_t out_sz = dtype_size(out_dtype);
     fast = fast && aligned(a.A, 16) && aligned(a.B, 16) && aligned(a.D, out_sz == 4 ? 16 : 8);
     fast = fast && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldd % 8 == 0 && a.K % 8 == 0 && a.a_skip % 8 == 0;
-    if (a.ident) fast = fast && a.d_h % 32 == 0;   // one 32-column MFMA tile never straddles two heads
+    const bool ident_tiles = !a.ident || a.d_h % 32 == 0;   // one 32-column MFMA tile never straddles two heads
+    const bool ident_vec = !a.ident || a.d_h % 8 == 0;
     // 32-bit buffer offsets: a 256-row tile must span less than 2 GiB in each operand
     const int64_t max_ld = (int64_t)1 << 21;
     fast = fast && a.lda < max_ld && a.ldd < max_ld && a.ldb < max_ld && (int64_t)a.K * a.ldb * 2 < ((int64_t)1 << 31);
     for (int g = 0; g < G; ++g) fast = fast && a.a_off[g] % 8 == 0 && group_cols[g] % 8 == 0;
 
-    if (fast) {
+    if (fast && ident_vec && g_tile_policy.load() == 0 && a.M <= kDecodeMaxT && a.K <= kDecodeMaxK) {
+        // a few tokens: stream the weights once, 32 output columns per workgroup
+        build_tiles(a, G, group_cols, kDecodeMaxT, 32);
+        a.sm = a.sn = 1;
+        if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_decode<F16, uint16_t>(a, st);
+        if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_decode<F16, float>(a, st);
+        if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_decode<BF16, uint16_t>(a, st);
+        if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_decode<BF16, float>(a, st);
+    }
+    if (fast && ident_tiles) {
         // big tiles when they still fill the chip, otherwise 128 x 128 tiles with two workgroups
         // per compute unit
         const int64_t mt256 = (a.M + 255) / 256;

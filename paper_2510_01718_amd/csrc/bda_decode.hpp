@@ -1,0 +1,159 @@
+// Small-T ("decode") kernel of libbda for gfx950: T <= 64 tokens.
+//
+// With a handful of tokens the projection is a stream over the weights: every element of C is read
+// exactly once and used for at most 64 multiply-adds, so the kernel is organised around that read
+// (bandwidth / latency bound), not around MFMA occupancy:
+//   * one workgroup per 32-column slice of the output, all K rows of it: its part of C
+//     (K x 64 bytes) goes global -> LDS in one burst of LDS DMA loads issued at kernel start;
+//   * slices are handed out so that neighbouring slices (which share 128-byte lines of C) run on
+//     the same die and meet in its L2;
+//   * the four waves split the k-steps; their partial sums are added in a fixed order through LDS,
+//     so the result does not depend on scheduling;
+//   * the token fragments come straight from global memory in MFMA operand layout (a row of the
+//     latent is k-contiguous), the identity slice is added in float32 after the reduction.
+#pragma once
+#include "bda_gemm_stream.hpp"
+
+namespace bda {
+
+constexpr int kDecodeMaxT = 64;
+constexpr int kDecodeMaxK = 1536;       // K x 64 bytes of LDS for the slice of C
+
+template <typename X, typename OutT>
+__global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, lhi = lane >> 5;
+
+    // slice owned by this workgroup: dies take contiguous runs of slices
+    const int per_xcd = (p.n_tiles + kNumXcd - 1) / kNumXcd;
+    const int slice = (int)(blockIdx.x % kNumXcd) * per_xcd + (int)(blockIdx.x / kNumXcd);
+    if (slice >= p.n_tiles) return;
+    int g = 0;
+    while (g + 1 < p.n_groups && slice >= p.tile_start[g + 1]) ++g;
+    const int rel0 = (slice - p.tile_start[g]) * 32;
+    const int64_t n0 = p.col_start[g] + rel0;
+    const int64_t left = p.col_start[g + 1] - n0;
+    const int cols_left = (int)(left > 32 ? 32 : left);
+    const int a_off = p.a_off[g];
+    const int T = (int)p.M;
+    const int nks = (p.K + 15) >> 4;                     // k-steps of 16
+    const int wgt_bytes = nks * 16 * 64;                 // LDS: [k][32 columns] 16-bit
+
+    // ---- the slice of C: K rows x 64 bytes, 16 rows per DMA instruction --------------------------
+    const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
+    {
+        const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
+        const int piece = lane & 3;
+        const uint32_t lane_off = piece * 8 < cols_left ? (uint32_t)(lane >> 2) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
+        const int n_instr = nks;                          // 16 rows each
+        for (int i = wave * 2; i < n_instr; i += 8) {     // two instructions per wave per round
+            const uint32_t v0 = lane_off + (uint32_t)(i * 16) * row_bytes;
+            const uint32_t v1 = i + 1 < n_instr ? lane_off + (uint32_t)((i + 1) * 16) * row_bytes : kBadOffset;
+            lds_dma2(rB, (uint32_t)(i * 1024), v0, v1);   // rows past K fall outside rB's range -> zeros
+        }
+    }
+
+    // ---- token fragments for this wave's k-steps (ks = wave, wave + 4, ...) --------------------------
+    const int n_tb = T > 32 ? 2 : 1;
+    const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    f32x16 acc[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[tb][r] = 0.0f;
+
+    // transposing-read addresses: 16-lane group gq, s = lane % 16: row 8 lhi + 4 rd + s/4,
+    // columns 16 (gq & 1) + 4 (s & 3) .. + 3
+    const int c_s = lane & 15, c_gq = lane >> 4;
+    const uint32_t w_rd = (uint32_t)((8 * lhi + (c_s >> 2)) * 64 + (16 * (c_gq & 1) + 4 * (c_s & 3)) * 2);
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+
+    // first the token loads of all this wave's k-steps (they overlap the DMA), in chunks of 6 k-steps
+    for (int ks0 = wave; ks0 < nks; ks0 += 4 * 6) {
+        u32x4 ft[6][2];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int ks = ks0 + 4 * i;
+            const int k = ks * 16 + 8 * lhi;
+            const int col = k < a_off ? k : k + p.a_skip;
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const bool ok = ks < nks && k < p.K && tb < n_tb;
+                ft[i][tb] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rA, ok ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset, 0, 0);
+            }
+        }
+        if (ks0 == wave) {                                // the slice of C must have landed (all waves)
+            wait_vmcnt<12>();                             // the 12 token loads above may still fly
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int ks = ks0 + 4 * i;
+            if (ks < nks) {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024 + 256));
+                const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+                const u32x4 fw = {lo2[0], lo2[1], hi2[0], hi2[1]};
+                acc[0] = X::mfma(fw, ft[i][0], acc[0]);
+                if (n_tb > 1) acc[1] = X::mfma(fw, ft[i][1], acc[1]);
+            }
+        }
+    }
+    if (wave >= nks) {                                    // a wave without k-steps still joins the barrier
+        wait_vmcnt<0>();
+        __syncthreads();
+    }
+
+    // ---- fixed-order reduction over the four waves ------------------------------------------------
+    float* part = (float*)(smem + wgt_bytes);            // [wave][tb][r][lane]
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+        if (tb < n_tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[((wave * 2 + tb) * 16 + r) * 64 + lane] = acc[tb][r];
+    __syncthreads();
+    // wave w finishes accumulator rows 4 w .. 4 w + 3 = output columns 8 w + 4 lhi + 0..3
+    const int col = 8 * wave + 4 * lhi;
+    const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
+                                                ((int64_t)(T - 1) * p.ldd + cols_left) * (int64_t)sizeof(OutT));
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        if (tb >= n_tb) break;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) s += part[((w * 2 + tb) * 16 + 4 * wave + e) * 64 + lane];
+            v[e] = s;
+        }
+        const int t = tb * 32 + l31;
+        if (p.ident) {
+            const int j = (rel0 + col) % p.d_h;
+            const u32x2 idv = __builtin_amdgcn_raw_buffer_load_b64(
+                rA, col < cols_left ? (uint32_t)t * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+            v[0] += X::to_f32((uint16_t)(idv[0] & 0xffffu));
+            v[1] += X::to_f32((uint16_t)(idv[0] >> 16));
+            v[2] += X::to_f32((uint16_t)(idv[1] & 0xffffu));
+            v[3] += X::to_f32((uint16_t)(idv[1] >> 16));
+        }
+        const uint32_t off = col < cols_left ? (uint32_t)t * (uint32_t)(p.ldd * sizeof(OutT)) + (uint32_t)col * (uint32_t)sizeof(OutT) : kBadOffset;
+        if constexpr (sizeof(OutT) == 4) {
+            const f32x4 vf = {v[0], v[1], v[2], v[3]};
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, off, 0, 0);
+        } else {
+            u32x2 o;
+            o[0] = (uint32_t)X::from_f32(v[0]) | ((uint32_t)X::from_f32(v[1]) << 16);
+            o[1] = (uint32_t)X::from_f32(v[2]) | ((uint32_t)X::from_f32(v[3]) << 16);
+            __builtin_amdgcn_raw_buffer_store_b64(o, rD, off, 0, 0);
+        }
+    }
+}
+
+}  // namespace bda

@@ -55,6 +55,19 @@ def test_config3_decode_shapes(T):
     _run_kv_case(w, [0, 0])
 
 
+@pytest.mark.parametrize("T", [1, 7, 33, 64])
+@pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.BF16, wl.F32)])
+def test_decode_kernel_groups_and_offsets(T, dtype, out_dtype):
+    # the small-T kernel: two groups with different windows, a group that ends inside a 32-column
+    # slice (40 columns), head width 8 ... and the V2-Lite head shape
+    w = wl.custom_kv_workload("dec_a", T=T, d_c=512, d_h=128, H=[3, 2], std=0.02, rms_norm=True, dtype=dtype, seed=40 + T)
+    _run_kv_case(w, [64, 384], out_dtype=out_dtype)
+    w = wl.custom_kv_workload("dec_b", T=T, d_c=96, d_h=40, H=[1, 2], std=0.1, rms_norm=True, dtype=dtype, seed=41 + T)
+    _run_kv_case(w, [56, 0], out_dtype=out_dtype)
+    w = wl.custom_kv_workload("dec_c", T=T, d_c=1152, d_h=64, H=[5], std=0.02, rms_norm=True, dtype=dtype, seed=42 + T)
+    _run_kv_case(w, [512], out_dtype=out_dtype)
+
+
 @pytest.mark.parametrize("policy", [1, 2])
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
 @pytest.mark.parametrize("offs", [[0, 0], [384, 384], [0, 384], [64, 200]])
