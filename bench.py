@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run three 256 MiB device copies (reference for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (the path shards by tokens or heads with no "
@@ -69,6 +71,14 @@ def main() -> int:
         return torch.from_numpy(a).cuda()
 
     tdt = {wl.F16: torch.float16, wl.BF16: torch.int16, wl.F32: torch.float32}
+
+    if args.calib_copy:
+        xs = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        ys = torch.empty_like(xs)
+        for _ in range(3):
+            ys.copy_(xs)
+        torch.cuda.synchronize()
+        del xs, ys
 
     # ------------------------------------------------------------------ main workload (config 2)
     w = wl.kv_workload("v2lite")
