@@ -1,6 +1,7 @@
 // Device entry points of libbda: argument validation, tile-grid construction and kernel launch.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 
@@ -62,6 +63,21 @@ int launch_stream(GemmArgs& a, hipStream_t st)
     constexpr int lds = kStreamNS * (256 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
     auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS, 0>;
     if (int rc = set_max_lds(kern, lds, once)) return rc;
+    a.n_super_m = (a.m_tiles + a.sm - 1) / a.sm;
+    a.n_super_n = (a.n_tiles + a.sn - 1) / a.sn;
+    a.sn_shift = 0;
+    while ((1 << a.sn_shift) < a.sn) ++a.sn_shift;
+    a.dh_magic = a.d_h > 0 ? (((uint64_t)1 << 40) + a.d_h - 1) / a.d_h : 0;
+    {
+        const int64_t total = (int64_t)a.n_super_m * a.n_super_n;
+        a.rounds = (int)((total + kNumXcd - 1) / kNumXcd);
+        for (int x = 0; x < kNumXcd; ++x) {
+            const int64_t first = std::min<int64_t>((int64_t)x * a.rounds, total);
+            a.xcd_q0[x] = (int)(first % a.n_super_m);
+            a.xcd_r0[x] = (int)(first / a.n_super_m);
+            a.xcd_count[x] = (int)std::min<int64_t>(a.rounds, total - first);
+        }
+    }
     hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
@@ -160,7 +176,9 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
             build_tiles(a, G, group_cols, 128, 128);
             choose_super(a, 2 * kSlotsPerXcd);
         }
-        const bool stream = big && (a.K + kStreamSK - 1) / kStreamSK + a.n_stage_id >= kStreamNS;
+        bool stream = big && (a.K + kStreamSK - 1) / kStreamSK + a.n_stage_id >= kStreamNS;
+        for (int g = 0; g < G; ++g) stream = stream && group_cols[g] < (1 << 24);   // exact x % d_h by multiplication
+        stream = stream && a.d_h < (1 << 16);
 #define BDA_LAUNCH(X, O)                                      \
     return stream ? launch_stream<X, O>(a, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
         if (dtype == BDA_F16 && out_dtype == BDA_F16) { BDA_LAUNCH(F16, uint16_t); }

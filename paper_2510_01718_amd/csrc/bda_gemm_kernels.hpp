@@ -38,6 +38,12 @@ struct GemmArgs {
     int m_tiles, n_tiles;            // tile grid (n_tiles counts the tiles of all groups)
     int sm, sn;                      // super-tile shape handed to one die at a time (sm*sn = 32)
     int n_stage_id;                  // streaming kernel: identity stages per tile (0 if ident == 0)
+    int n_super_m, n_super_n;        // streaming kernel: super-tile grid, ceil(m_tiles / sm) x ceil(n_tiles / sn)
+    int sn_shift;                    // streaming kernel: log2(sn)
+    uint64_t dh_magic;               // streaming kernel: ceil(2^40 / d_h), for x % d_h with x < 2^24
+    int rounds;                      // streaming kernel: super-tiles per die, ceil(n_super_m n_super_n / 8)
+    int xcd_q0[8], xcd_r0[8];        // streaming kernel: first super-tile of die x (token, column index)
+    int xcd_count[8];                // streaming kernel: super-tiles of die x (<= rounds)
     int tile_start[kMaxGroups + 1];  // first column tile of each group
     int64_t col_start[kMaxGroups + 1];  // first output column of each group
     int a_off[kMaxGroups];           // basis window start of each group (k >= a_off -> k + a_skip)

@@ -60,6 +60,16 @@ __device__ __forceinline__ void lds_dma2(u32x4 rsrc, uint32_t lds_base, uint32_t
         : "s"(lds_base), "v"(v0), "v"(v1), "s"(rsrc)
         : "memory", "m0", "scc");
 }
+__device__ __forceinline__ void lds_dma1(u32x4 rsrc, uint32_t lds_addr, uint32_t v0)
+{
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "buffer_load_dwordx4 %1, %2, 0 offen lds\n\t"
+        :
+        : "s"(lds_addr), "v"(v0), "s"(rsrc)
+        : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void lds_dma(u32x4 rsrc, uint32_t lds_base, const uint32_t (&v)[N])
 {
@@ -97,14 +107,23 @@ __device__ __forceinline__ int tok_swz(int r)
 // different banks.
 __device__ __forceinline__ int wgt_swz(int k) { return (k & 3) * 5; }
 
+#ifdef BDA_TRACE
+__device__ unsigned long long bda_trace[8 * 1024];
+#define BDA_STAMP(tag) do { if constexpr (DBG & 16) { if (blockIdx.x == 9 && tr_n < 1020) { \
+    const unsigned long long tm_ = __builtin_readcyclecounter(); \
+    if (lane == 0) bda_trace[wave * 1024 + tr_n] = (tm_ << 8) | (tag); ++tr_n; } } } while (0)
+#else
+#define BDA_STAMP(tag) do { } while (0)
+#endif
+
 struct StreamTile {
     u32x4 rA, rB;              // producer descriptors (range 0 for a tile outside the grid)
     int64_t d_off;             // element offset of the tile's first output
     int64_t rows_left;         // valid token rows from the tile's first row (<= 0: none)
     int cols_left;             // valid columns of the tile (a group may end inside it; 0: none)
     int a_off;                 // basis window start of the tile's group
-    int rel0;                  // first column of the tile inside its group
     int j_lo;                  // first identity-slice column the tile needs
+    int rel_blk0;              // slice column of the first 32-column block of the calling wave's part
 };
 
 // DBG is for timing experiments only (0 in the library): bit 0 drops the result stores, bit 1 the
@@ -141,62 +160,114 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     constexpr int WAIT_AFTER_STORES = WAIT_STEADY + STORES < 63 ? WAIT_STEADY + STORES : 63;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
+    // The scalar kernel arguments are fetched here in one batch and made opaque, so that they live in
+    // registers; otherwise each use re-fetches its argument from memory and the per-tile set-up
+    // becomes a chain of dependent scalar loads.
+    struct {
+        const void *A, *B; void* D;
+        int64_t lda, ldb, ldd, M;
+        int K, n_groups, d_h, a_skip, ident, m_tiles, n_tiles, sm, sn, n_stage_id, n_super_m, n_super_n, sn_shift;
+        uint64_t dh_magic;
+        int ts1, ts2, rounds, xq0, xr0, xcount;
+    } q = {p.A, p.B, p.D, p.lda, p.ldb, p.ldd, p.M, p.K, p.n_groups, p.d_h, p.a_skip, p.ident, p.m_tiles, p.n_tiles,
+           p.sm, p.sn, p.n_stage_id, p.n_super_m, p.n_super_n, p.sn_shift, p.dh_magic, p.tile_start[1], p.tile_start[2],
+           p.rounds, p.xcd_q0[blockIdx.x % kNumXcd], p.xcd_r0[blockIdx.x % kNumXcd], p.xcd_count[blockIdx.x % kNumXcd]};
+    asm volatile("" : "+s"(q.A), "+s"(q.B), "+s"(q.D), "+s"(q.lda), "+s"(q.ldb), "+s"(q.ldd), "+s"(q.M), "+s"(q.dh_magic));
+    asm volatile("" : "+s"(q.K), "+s"(q.n_groups), "+s"(q.d_h), "+s"(q.a_skip), "+s"(q.ident), "+s"(q.m_tiles), "+s"(q.n_tiles),
+                 "+s"(q.sm), "+s"(q.sn), "+s"(q.n_stage_id), "+s"(q.n_super_m), "+s"(q.n_super_n), "+s"(q.sn_shift),
+                 "+s"(q.ts1), "+s"(q.ts2), "+s"(q.rounds), "+s"(q.xq0), "+s"(q.xr0), "+s"(q.xcount));
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
+    int tr_n = 0;
+    (void)tr_n;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wt = wave / WN, wn = wave % WN;
     const int l31 = lane & 31, lhi = lane >> 5;
 
-    const int nk = (p.K + kStageK - 1) / kStageK;
-    const int n_id = p.ident ? p.n_stage_id : 0;
+    const int nk = (q.K + kStageK - 1) / kStageK;
+    const int n_id = q.ident ? q.n_stage_id : 0;
     const int S = nk + n_id;
-    const int n_super_n = (p.n_tiles + p.sn - 1) / p.sn;
-    const int n_super_m = (p.m_tiles + p.sm - 1) / p.sm;
-    const int total_super = n_super_m * n_super_n;
-    const int n_rounds = (total_super + kNumXcd - 1) / kNumXcd;
     const int xcd = blockIdx.x % kNumXcd;
     const int slot = blockIdx.x / kNumXcd;
-    const int slot_m = slot / p.sn, slot_n = slot % p.sn;
+    const int slot_m = slot >> q.sn_shift, slot_n = slot & (q.sn - 1);
+    // x % d_h for 0 <= x < 2^24, d_h < 2^16: floor(x M / 2^40) with M = ceil(2^40 / d_h) is exact
+    auto mod_dh = [&](int x) { return x - (int)(((uint64_t)(uint32_t)x * q.dh_magic) >> 40) * q.d_h; };
 
-    // ---- tile set-up (scalar; once per tile) ------------------------------------------------------
-    auto setup = [&](int round) -> StreamTile {
-        StreamTile t;
-        const int sidx = round * kNumXcd + xcd;
-        const int mt = (sidx / n_super_n) * p.sm + slot_m;
-        const int nt = (sidx % n_super_n) * p.sn + slot_n;
-        const bool valid = round < n_rounds && sidx < total_super && mt < p.m_tiles && nt < p.n_tiles;
+    // ---- tile set-up (scalar) -----------------------------------------------------------------------
+    // Super-tiles (sm x sn tiles) are numbered down the token dimension first; die x works through
+    // the numbers [x R, (x + 1) R), R = rounds.  A workgroup keeps its slot inside the super-tile, so
+    // from one round to the next it usually moves down by sm token tiles and keeps its columns: the
+    // die's L2 keeps the sn weight tiles and only the token tiles stream, and the column half of the
+    // set-up (group lookup, weight descriptor) is done only when the column changes.
+    const int n_rounds = q.rounds;
+    int su_q = q.xq0, su_r = q.xr0, su_left = q.xcount;
+    struct { u32x4 rB; int64_t n0; int cols_left, a_off, j_lo, rel_blk0; bool ok; } col;
+    bool col_dirty = true;
+    auto setup_cols = [&]() {
+        const int nt = su_r * q.sn + slot_n;
+        col.ok = nt < q.n_tiles;
         int g = 0;
-        while (g + 1 < p.n_groups && nt >= p.tile_start[g + 1]) ++g;
-        const int rel0 = valid ? (nt - p.tile_start[g]) * BN : 0;
-        const int64_t n0 = valid ? p.col_start[g] + rel0 : 0;
-        const int64_t left = p.col_start[g + 1] - n0;
+        if (q.n_groups <= 2) g = (q.n_groups == 2 && nt >= q.ts1) ? 1 : 0;
+        else if (nt >= q.ts1) { g = 1; while (g + 1 < q.n_groups && nt >= p.tile_start[g + 1]) ++g; }
+        const int rel0 = col.ok ? (nt - p.tile_start[g]) * BN : 0;
+        col.n0 = col.ok ? p.col_start[g] + rel0 : 0;
+        const int64_t left = p.col_start[g + 1] - col.n0;
+        col.cols_left = col.ok ? (int)(left > BN ? BN : left) : 0;
+        col.a_off = p.a_off[g];
+        const int r0 = q.ident ? mod_dh(rel0) : 0;
+        col.j_lo = (q.ident && (q.d_h & (BN - 1)) == 0) ? r0 : 0;
+        col.rel_blk0 = q.ident ? mod_dh(r0 + wn * (32 * TN)) : 0;
+        col.rB = make_rsrc_words((const char*)q.B + col.n0 * 2,
+                                 col.ok ? ((int64_t)(q.K - 1) * q.ldb + col.cols_left) * 2 : 0);
+    };
+    auto setup = [&]() -> StreamTile {
+        StreamTile t;
+        if (su_left <= 0) {                   // past the die's last super-tile: a tile that fetches and stores nothing
+            t.rA = make_rsrc_words(q.A, 0);
+            t.rB = make_rsrc_words(q.B, 0);
+            t.d_off = 0; t.rows_left = 0; t.cols_left = 0; t.a_off = 0; t.j_lo = 0; t.rel_blk0 = 0;
+            return t;
+        }
+        if (col_dirty) setup_cols();
+        const int mt = su_q * q.sm + slot_m;
+        const bool valid = su_left > 0 && col.ok && mt < q.m_tiles;
         const int64_t t0 = valid ? (int64_t)mt * BT : 0;
-        t.rows_left = valid ? p.M - t0 : 0;
-        t.cols_left = valid ? (int)(left > BN ? BN : left) : 0;
-        t.a_off = p.a_off[g];
-        t.rel0 = rel0;
-        t.j_lo = (p.ident && (p.d_h % BN) == 0) ? rel0 % p.d_h : 0;
-        t.d_off = t0 * p.ldd + n0;
-        t.rA = make_rsrc_words((const char*)p.A + t0 * p.lda * 2,
-                               valid ? ((t.rows_left - 1) * p.lda + p.K + p.a_skip) * 2 : 0);
-        t.rB = make_rsrc_words((const char*)p.B + n0 * 2,
-                               valid ? ((int64_t)(p.K - 1) * p.ldb + t.cols_left) * 2 : 0);
+        t.rows_left = valid ? q.M - t0 : 0;
+        t.cols_left = valid ? col.cols_left : 0;
+        t.a_off = col.a_off;
+        t.j_lo = col.j_lo;
+        t.rel_blk0 = col.rel_blk0;
+        t.d_off = t0 * q.ldd + col.n0;
+        t.rA = make_rsrc_words((const char*)q.A + t0 * q.lda * 2,
+                               valid ? ((t.rows_left - 1) * q.lda + q.K + q.a_skip) * 2 : 0);
+        t.rB = col.rB;
+        if (!valid) t.rB[2] = 0;
+        // next super-tile of this die
+        --su_left;
+        col_dirty = false;
+        if (++su_q == q.n_super_m) { su_q = 0; ++su_r; col_dirty = true; }
         return t;
     };
 
-    // ---- per-lane constants ------------------------------------------------------------------
-    // identity fragments (row operand): lane (row i = l31, half lhi) holds k' = 16 v + 8 lhi + e
-    u32x4 idf[2];
+    // identity fragments (row operand): lane (row i = l31, half lhi) holds k' = 16 v + 8 lhi + e.
+    // Built where they are used, from a copy of the lane id the optimiser cannot see through, so that
+    // they do not occupy registers during the regular stages.
+    auto make_idf = [&](u32x4 (&idf)[2]) {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int r31 = ln & 31, rhi = ln >> 5;
 #pragma unroll
-    for (int v = 0; v < 2; ++v)
+        for (int v = 0; v < 2; ++v)
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const int k0 = 16 * v + 8 * lhi + 2 * w;
-            idf[v][w] = (k0 == l31 ? IdentityFrag<X>::one : 0u) | (k0 + 1 == l31 ? IdentityFrag<X>::one << 16 : 0u);
-        }
+            for (int w = 0; w < 4; ++w) {
+                const int k0 = 16 * v + 8 * rhi + 2 * w;
+                idf[v][w] = (k0 == r31 ? IdentityFrag<X>::one : 0u) | (k0 + 1 == r31 ? IdentityFrag<X>::one << 16 : 0u);
+            }
+    };
 
     // producer, token tile: load j of wave w fills LDS rows RPI (w PIT + j) + lane/PR, position lane%PR
-    const uint32_t tok_row_bytes = (uint32_t)(p.lda * 2);
+    const uint32_t tok_row_bytes = (uint32_t)(q.lda * 2);
     const uint32_t p_tok_row_off = (uint32_t)(wave * (RPI * PIT) + lane / PR) * tok_row_bytes;
     // column of this lane's piece inside the stage; the swizzle sees row bits 0..3, of which bit 3
     // alternates with j when a load covers only 8 rows
@@ -204,7 +275,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
 #pragma unroll
     for (int j = 0; j < 2; ++j) p_tok_k8[j] = ((lane % PR) ^ tok_swz<SK>((lane / PR + RPI * j) & 15)) * 8;
     // producer, weight tile: load j of wave w fills k rows 2 (w PIW + j) + lane/32, position lane%32
-    const uint32_t wgt_row_bytes = (uint32_t)(p.ldb * 2);
+    const uint32_t wgt_row_bytes = (uint32_t)(q.ldb * 2);
     const uint32_t p_wgt_row_off = (uint32_t)(wave * (2 * PIW) + (lane >> 5)) * wgt_row_bytes;
     int p_wgt_c[2];                                   // the swizzle sees k & 3 = (2 j + lane/32) & 3
 #pragma unroll
@@ -212,10 +283,8 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     static_assert((RPI * PIT) % 16 == 0 && (2 * PIW) % 4 == 0, "per-wave row blocks must keep the swizzle phase");
 
     // consumer, token fragments: row = wt*32*TT + ti*32 + l31, piece q = 2 ks + lhi
-    uint32_t c_tok[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        c_tok[ks] = (uint32_t)((wt * (32 * TT) + l31) * RB + (((2 * ks + lhi) ^ tok_swz<SK>(l31 & 15)) << 4));
+    // piece (2 ks + lhi) ^ swz = ((lhi ^ swz) ^ (ks << 1)): k-step ks is the k-step 0 address with bit 5 + ... flipped
+    const uint32_t c_tok0 = (uint32_t)((wt * (32 * TT) + l31) * RB + ((lhi ^ tok_swz<SK>(l31 & 15)) << 4));
     // consumer, weight fragments (transposing read): 16-lane group gq = lane/16, s = lane%16:
     // k = 16 ks + 8 lhi + 4 rd + s/4, columns wn*32*TN + ni*32 + 16 (gq&1) + 4 (s&3) .. +3
     const int c_s = lane & 15, c_gq = lane >> 4;
@@ -230,19 +299,18 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     // ---- producer: stage `k` of tile `t` into LDS slot `g & 3` -------------------------------------
     // Always issues LOADS loads per thread; whatever has nothing to fetch (weights of an identity
     // stage, columns past the group's end, a tile outside the grid) uses an out-of-range offset.
-    auto produce = [&](const StreamTile& t, int k, int g) {
-        uint32_t tv[PIT], wv[PIW];
+    auto produce_addr = [&](const StreamTile& t, int k, uint32_t (&tv)[PIT], uint32_t (&wv)[PIW]) {
 #pragma unroll
         for (int j = 0; j < PIT; ++j) {
             int col, lim_ok;
             if (k < nk) {
                 const int kk = k * SK + p_tok_k8[j & 1];
-                col = kk < t.a_off ? kk : kk + p.a_skip;
-                lim_ok = kk < p.K;
+                col = kk < t.a_off ? kk : kk + q.a_skip;
+                lim_ok = kk < q.K;
             } else {
                 const int jc = t.j_lo + (k - nk) * SK + p_tok_k8[j & 1];
                 col = t.a_off + jc;
-                lim_ok = jc < p.d_h;
+                lim_ok = jc < q.d_h;
             }
             tv[j] = lim_ok ? p_tok_row_off + (uint32_t)(RPI * j) * tok_row_bytes + (uint32_t)col * 2u : kBadOffset;
         }
@@ -251,6 +319,18 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         for (int j = 0; j < PIW; ++j)
             wv[j] = p_wgt_c[j & 1] * 8 < t.cols_left ? wbase + (uint32_t)(2 * j) * wgt_row_bytes + (uint32_t)p_wgt_c[j & 1] * 16u
                                                       : kBadOffset;
+    };
+    // load j (0 .. LOADS-1) of a stage whose addresses produce_addr has computed
+    auto issue_load = [&](const StreamTile& t, int g, int j, const uint32_t (&tv)[PIT], const uint32_t (&wv)[PIW]) {
+        if constexpr (!(DBG & 4)) {
+            const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
+            if (j < PIT) lds_dma1(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, tv[j]);
+            else lds_dma1(t.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * (j - PIT), wv[j - PIT]);
+        }
+    };
+    auto produce = [&](const StreamTile& t, int k, int g) {
+        uint32_t tv[PIT], wv[PIW];
+        produce_addr(t, k, tv, wv);
         if constexpr (!(DBG & 4)) {
             const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
             lds_dma<PIT>(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT), tv);
@@ -289,7 +369,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     };
     auto read_t = [&](uint32_t sbase, int ks, u32x4 (&ft)[TT]) {
 #pragma unroll
-        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(smem + sbase + c_tok[ks] + ti * (32 * RB));
+        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(smem + ((sbase + c_tok0) ^ (uint32_t)(ks << 5)) + ti * (32 * RB));
     };
     auto mma_regular = [&](const u32x4 (&fw)[TN], const u32x4 (&ft)[TT]) {
 #pragma unroll
@@ -297,18 +377,37 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
 #pragma unroll
             for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw[ni], ft[ti], acc[ni][ti]);
     };
-    int rel_wave = 0;
-    auto mma_identity = [&](int col0, const u32x4 (&ft)[TT]) {
+    int rel_blk[TN] = {};                     // slice column of each 32-column block of this wave's tile part
+    auto mma_identity = [&](const u32x4 (&idf)[2], int col0, const u32x4 (&ft)[TT]) {
         // col0: first of the 16 slice columns this k-step holds
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {
-            const int d = col0 - (rel_wave + 32 * ni) % p.d_h;
+            const int d = col0 - rel_blk[ni];
             if (d == 0 || d == 16) {
                 const u32x4 f = d == 0 ? idf[0] : idf[1];
 #pragma unroll
                 for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(f, ft[ti], acc[ni][ti]);
             }
         }
+    };
+    // the same products with this stage's loads j0 .. j0 + n - 1 issued between them, so that the
+    // address unit sees a steady trickle instead of every wave's loads at once
+    auto mma_regular_loads = [&](const u32x4 (&fw)[TN], const u32x4 (&ft)[TT], const StreamTile& pt, int g, int j0,
+                                 const uint32_t (&tv)[PIT], const uint32_t (&wv)[PIW]) {
+        constexpr int NL = LOADS / 2, EVERY = (TN * TT) / NL > 0 ? (TN * TT) / NL : 1;
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int ti = 0; ti < TT; ++ti) {
+                acc[ni][ti] = mm(fw[ni], ft[ti], acc[ni][ti]);
+                const int m = ni * TT + ti;
+                if (m % EVERY == EVERY - 1 && m / EVERY < NL) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue_load(pt, g, j0 + m / EVERY, tv, wv);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        static_assert(NL <= TN * TT, "more loads than products in a k-step");
     };
     auto slot_base = [&](int g) { return (uint32_t)((g & (kStages - 1)) * STAGE_BYTES); };
     auto clear_acc = [&]() {
@@ -326,15 +425,57 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         const uint32_t sb = slot_base(g), nb = slot_base(g + 1);
         const bool next_regular = kc + 1 < nk || kc + 1 == S;
         const int jc = cur.j_lo + (kc - nk) * SK;
+        u32x4 idf[2];
+        if constexpr (!REG) make_idf(idf);
+        if constexpr (!(DBG & 8)) {
+            static_assert(KS % 2 == 0, "fragment sets alternate");
+            BDA_STAMP(1);
+#pragma unroll
+            for (int ks = 0; ks + 2 < KS; ++ks) {
+                if (ks % 2 == 0) {
+                    if constexpr (REG) { read_w(sb, ks + 1, fw1); read_t(sb, ks + 1, ft1); mma_regular(fw0, ft0); }
+                    else { read_t(sb, ks + 1, ft1); mma_identity(idf, jc + 16 * ks, ft0); }
+                } else {
+                    if constexpr (REG) { read_w(sb, ks + 1, fw0); read_t(sb, ks + 1, ft0); mma_regular(fw1, ft1); }
+                    else { read_t(sb, ks + 1, ft0); mma_identity(idf, jc + 16 * ks, ft1); }
+                }
+            }
+            // last read of this stage's slot, then the slot is free once every wave is here
+            if constexpr (REG) read_w(sb, KS - 1, fw1);
+            read_t(sb, KS - 1, ft1);
+            BDA_STAMP(2);
+            if (relaxed) wait_vmcnt<WAIT_AFTER_STORES>(); else wait_vmcnt<WAIT_STEADY>();
+            BDA_STAMP(3);
+            __syncthreads();
+            BDA_STAMP(4);
+            uint32_t tv[PIT], wv[PIW];
+            produce_addr(pt, pk, tv, wv);
+            if constexpr (REG) mma_regular_loads(fw0, ft0, pt, g, 0, tv, wv);
+            else {
+                mma_identity(idf, jc + 16 * (KS - 2), ft0);
+#pragma unroll
+                for (int j = 0; j < LOADS / 2; ++j) issue_load(pt, g, j, tv, wv);
+            }
+            BDA_STAMP(5);
+            if (next_regular) read_w(nb, 0, fw0);
+            read_t(nb, 0, ft0);
+            if constexpr (REG) mma_regular_loads(fw1, ft1, pt, g, LOADS / 2, tv, wv);
+            else {
+                mma_identity(idf, jc + 16 * (KS - 1), ft1);
+#pragma unroll
+                for (int j = LOADS / 2; j < LOADS; ++j) issue_load(pt, g, j, tv, wv);
+            }
+            return;
+        }
         // k-steps 0 .. KS-2: read the next k-step's fragments, multiply the current ones
 #pragma unroll
         for (int ks = 0; ks + 1 < KS; ++ks) {
             if (ks % 2 == 0) {
                 if constexpr (REG) { read_w(sb, ks + 1, fw1); read_t(sb, ks + 1, ft1); mma_regular(fw0, ft0); }
-                else { read_t(sb, ks + 1, ft1); mma_identity(jc + 16 * ks, ft0); }
+                else { read_t(sb, ks + 1, ft1); mma_identity(idf, jc + 16 * ks, ft0); }
             } else {
                 if constexpr (REG) { read_w(sb, ks + 1, fw0); read_t(sb, ks + 1, ft0); mma_regular(fw1, ft1); }
-                else { read_t(sb, ks + 1, ft0); mma_identity(jc + 16 * ks, ft1); }
+                else { read_t(sb, ks + 1, ft0); mma_identity(idf, jc + 16 * ks, ft1); }
             }
         }
         // stage g + 1 must have landed for every wave, and every wave must be done with stage g's
@@ -347,19 +488,28 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         if constexpr (REG)
             mma_regular(fw1, ft1);            // KS is even: the last k-step sits in the second set
         else
-            mma_identity(jc + 16 * (KS - 1), ft1);
+            mma_identity(idf, jc + 16 * (KS - 1), ft1);
     };
 
-    StreamTile cur = setup(0);
+    BDA_STAMP(0);
+    StreamTile cur = setup();
     int g = 0;
     // prologue: the first kStages stages of the first tile
 #pragma unroll 1
-    for (int k = 0; k < kStages; ++k) produce(cur, k, k);
+    BDA_STAMP(9);
+    for (int k = 0; k < kStages; ++k) {
+        produce(cur, k, k);
+        if (k == 0) __builtin_amdgcn_s_barrier();   // the first stage of all waves goes ahead of everything else
+    }
+    BDA_STAMP(10);
     clear_acc();
     wait_vmcnt<(kStages - 1) * LOADS>();
+    BDA_STAMP(11);
     __syncthreads();
+    BDA_STAMP(12);
     read_w(slot_base(0), 0, fw0);
     read_t(slot_base(0), 0, ft0);
+    BDA_STAMP(13);
 
     const std::true_type REGULAR{};
     const std::false_type IDENTITY{};
@@ -368,8 +518,14 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     const int i_same = split > nk ? split : nk;
 #pragma unroll 1
     for (int round = 0; round < n_rounds; ++round) {
-        const StreamTile nxt = setup(round + 1);
-        rel_wave = (cur.rel0 + wn * (32 * TN)) % (p.d_h > 0 ? p.d_h : 1);
+        const StreamTile nxt = setup();
+        BDA_STAMP(14);
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) {      // d_h >= 32 is a multiple of 32 and rel_blk0 < d_h
+            rel_blk[ni] = cur.rel_blk0 + 32 * ni;
+            if (rel_blk[ni] >= q.d_h) rel_blk[ni] -= q.d_h;
+            if (rel_blk[ni] >= q.d_h) rel_blk[ni] -= q.d_h;
+        }
         const bool after_tile = round > 0;
         int kc = 0;
 #pragma unroll 1
@@ -381,12 +537,13 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
 #pragma unroll 1
         for (; kc < S; ++kc, ++g) stage(IDENTITY, cur, kc, g, nxt, kc - split, after_tile && kc < (kAhead > 1 ? kAhead : 1));
 
+        BDA_STAMP(6);
         // ---- epilogue ---------------------------------------------------------------------------
         // rows past the end of the tensor and tiles outside the grid fall outside rD's range
         const __amdgpu_buffer_rsrc_t rD = make_rsrc(
-            (char*)p.D + cur.d_off * (int64_t)sizeof(OutT),
-            cur.cols_left > 0 ? ((cur.rows_left - 1) * p.ldd + cur.cols_left) * (int64_t)sizeof(OutT) : 0);
-        const uint32_t ep_row_step = 32u * (uint32_t)(p.ldd * sizeof(OutT));
+            (char*)q.D + cur.d_off * (int64_t)sizeof(OutT),
+            cur.cols_left > 0 ? ((cur.rows_left - 1) * q.ldd + cur.cols_left) * (int64_t)sizeof(OutT) : 0);
+        const uint32_t ep_row_step = 32u * (uint32_t)(q.ldd * sizeof(OutT));
         const bool full = cur.cols_left == BN;      // uniform; a group may end inside its last tile
         if constexpr (DBG & 1) {
             float sum = 0.f;
@@ -398,7 +555,9 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                     for (int r = 0; r < 16; ++r) sum += acc[ni][ti][r];
             if (sum == 12345.678f) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, sum), rD, 0, 0, 0);
         } else if constexpr (sizeof(OutT) == 4) {
-            uint32_t ep_row = (uint32_t)(wt * (32 * TT) + l31) * (uint32_t)(p.ldd * 4) + (uint32_t)(wn * (32 * TN) + lhi * 4) * 4u;
+            int eln = lane;
+            asm volatile("" : "+v"(eln));
+            uint32_t ep_row = (uint32_t)(wt * (32 * TT) + (eln & 31)) * (uint32_t)(q.ldd * 4) + (uint32_t)(wn * (32 * TN) + (eln >> 5) * 4) * 4u;
 #pragma unroll
             for (int ti = 0; ti < TT; ++ti) {
                 if (ti) ep_row += ep_row_step;
@@ -424,11 +583,14 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
             // round in a 4 KiB LDS region private to the wave, so that 8 consecutive lanes store one
             // full 128-byte line of a row (the memory pipeline works on whole lines).
             unsigned char* stag = smem + kStages * STAGE_BYTES + wave * 4096;
-            const int st_wr = l31 * 128;                                    // + ((chunk ^ sw) << 4)
-            const int st_sw = (l31 ^ (l31 >> 3)) & 7;
-            const int rd_row = lane >> 3, rd_chunk = lane & 7;
-            uint32_t g_row = (uint32_t)(wt * (32 * TT) + rd_row) * (uint32_t)(p.ldd * 2) + (uint32_t)(wn * (32 * TN) + rd_chunk * 8) * 2u;
-            const uint32_t g_step8 = 8u * (uint32_t)(p.ldd * 2);
+            int eln = lane;                       // opaque copy: keeps these constants out of the k loops
+            asm volatile("" : "+v"(eln));
+            const int e31 = eln & 31;
+            const int st_wr = e31 * 128;                                    // + ((chunk ^ sw) << 4)
+            const int st_sw = (e31 ^ (e31 >> 3)) & 7;
+            const int rd_row = eln >> 3, rd_chunk = eln & 7;
+            uint32_t g_row = (uint32_t)(wt * (32 * TT) + rd_row) * (uint32_t)(q.ldd * 2) + (uint32_t)(wn * (32 * TN) + rd_chunk * 8) * 2u;
+            const uint32_t g_step8 = 8u * (uint32_t)(q.ldd * 2);
 #pragma unroll
             for (int ti = 0; ti < TT; ++ti) {
 #pragma unroll
@@ -450,7 +612,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                             const u32x2 s0 = __builtin_amdgcn_permlane32_swap(xv[0], yv[0], false, false);
                             const u32x2 s1 = __builtin_amdgcn_permlane32_swap(xv[1], yv[1], false, false);
                             const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
-                            const int chunk = nn * 4 + pr * 2 + lhi;        // 16-byte piece of the 64 columns
+                            const int chunk = nn * 4 + pr * 2 + (eln >> 5);  // 16-byte piece of the 64 columns
                             *(u32x4*)(stag + st_wr + ((chunk ^ st_sw) << 4)) = v;
                         }
                     }
@@ -466,10 +628,12 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                 }
             }
         }
+        BDA_STAMP(7);
         clear_acc();
         cur = nxt;
     }
     wait_vmcnt<0>();
+    BDA_STAMP(8);
 }
 
 }  // namespace bda
