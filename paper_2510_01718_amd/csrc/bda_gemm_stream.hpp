@@ -7,22 +7,33 @@
 //     buffer_load_dwordx4 ... lds (LDS DMA).  The token tile lands k-contiguous, the weight tile
 //     n-contiguous exactly as it lies in memory; the weight fragments are then read with the
 //     transposing LDS read ds_read_b64_tr_b16, so no shuffling instructions are spent on them.
-//   * The contraction is cut into stages of 32 and the LDS holds four stages.  Loads run three
-//     stages ahead of the MFMAs, and the stage sequence continues across output tiles: while the
-//     last stages of one tile are multiplied and its results are stored, the first stages of the
-//     workgroup's next tile are already in flight.  One barrier per stage.  Every workgroup runs
-//     the same number of tiles of the same number of stages (a tile position that falls outside
-//     the grid becomes a tile whose loads fetch nothing and whose stores are dropped), so the
-//     per-stage code has no tile bookkeeping in it.
+//   * The contraction is cut into stages of SK (64 in the library) and the LDS holds NS (2) stages.
+//     The stage sequence continues across output tiles: while the last stage of one tile is
+//     multiplied and its results are stored, the first stages of the workgroup's next tile are
+//     already in flight.  One barrier per stage, placed after the stage's last fragment read; the
+//     loads that refill the freed slot are issued one by one between the MFMAs of the stage's last
+//     two k-steps, so that no wave sits in the memory pipeline's queue with nothing else to issue.
+//     Every workgroup runs the same number of tiles of the same number of stages (a tile position
+//     that falls outside the grid becomes a tile whose loads fetch nothing and whose stores are
+//     dropped), so the per-stage code has no tile bookkeeping in it.
 //   * Bank conflicts are avoided by permuting which 16-byte piece each lane of a load fetches (the
 //     LDS image of one load instruction is always lane-linear), so the tiles need no padding.
-//   * 16-bit results are exchanged between the two half-waves (v_permlane32_swap) so that every
-//     lane stores 16 contiguous bytes.
+//   * 16-bit results are exchanged between the two half-waves (v_permlane32_swap) and turned round
+//     in a small per-wave LDS region so that eight lanes store one full 128-byte line.
+//   * Tile order: super-tiles of sm x sn tiles are numbered down the token dimension first and die x
+//     takes a contiguous range of them, so a workgroup usually keeps its columns from one tile to
+//     the next: the die's L2 keeps the weight tiles, and only the row half of the set-up is redone.
 //
 // The LDS DMA loads are issued from inline assembly: the compiler would otherwise wait for ALL
 // outstanding loads before any LDS read, which would serialise the stages.  Their completion is
 // tracked by hand with s_waitcnt vmcnt(n); every wave issues the same number of loads per stage
-// (loads that have nothing to fetch use an out-of-range offset and return zeros).
+// (loads that have nothing to fetch use an out-of-range offset and return zeros).  For the same
+// reason the kernel must not spill: a register reload is a memory load the compiler does know
+// about, and it would wait for it - and with it for every DMA load - inside the k loop.  Values
+// needed only in one phase (identity fragments, store addresses) are therefore rebuilt there from
+// a copy of the lane id that the optimiser cannot see through.
+//
+// Defining BDA_TRACE adds per-wave time stamps (s_memtime) for profiling experiments.
 #pragma once
 #include <type_traits>
 
@@ -127,7 +138,7 @@ struct StreamTile {
 };
 
 // DBG is for timing experiments only (0 in the library): bit 0 drops the result stores, bit 1 the
-// MFMAs, bit 2 the global loads.
+// MFMAs, bit 2 the global loads, bit 4 records time stamps (with BDA_TRACE).
 //
 // WT x WN waves share the 256 x 256 tile: 2 x 2 waves of 128 x 128 (one wave per SIMD) or 2 x 4 waves
 // of 128 tokens x 64 columns (two waves per SIMD, so that one wave's LDS reads, barrier wait and
@@ -324,8 +335,8 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     auto issue_load = [&](const StreamTile& t, int g, int j, const uint32_t (&tv)[PIT], const uint32_t (&wv)[PIW]) {
         if constexpr (!(DBG & 4)) {
             const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
-            if (j < PIT) lds_dma1(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, tv[j]);
-            else lds_dma1(t.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * (j - PIT), wv[j - PIT]);
+            if (j < PIT) lds_dma1(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, tv[j < PIT ? j : 0]);
+            else lds_dma1(t.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * (j - PIT), wv[j >= PIT ? j - PIT : 0]);
         }
     };
     auto produce = [&](const StreamTile& t, int k, int g) {
@@ -427,49 +438,10 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         const int jc = cur.j_lo + (kc - nk) * SK;
         u32x4 idf[2];
         if constexpr (!REG) make_idf(idf);
-        if constexpr (!(DBG & 8)) {
-            static_assert(KS % 2 == 0, "fragment sets alternate");
-            BDA_STAMP(1);
+        static_assert(KS % 2 == 0, "fragment sets alternate");
+        BDA_STAMP(1);
 #pragma unroll
-            for (int ks = 0; ks + 2 < KS; ++ks) {
-                if (ks % 2 == 0) {
-                    if constexpr (REG) { read_w(sb, ks + 1, fw1); read_t(sb, ks + 1, ft1); mma_regular(fw0, ft0); }
-                    else { read_t(sb, ks + 1, ft1); mma_identity(idf, jc + 16 * ks, ft0); }
-                } else {
-                    if constexpr (REG) { read_w(sb, ks + 1, fw0); read_t(sb, ks + 1, ft0); mma_regular(fw1, ft1); }
-                    else { read_t(sb, ks + 1, ft0); mma_identity(idf, jc + 16 * ks, ft1); }
-                }
-            }
-            // last read of this stage's slot, then the slot is free once every wave is here
-            if constexpr (REG) read_w(sb, KS - 1, fw1);
-            read_t(sb, KS - 1, ft1);
-            BDA_STAMP(2);
-            if (relaxed) wait_vmcnt<WAIT_AFTER_STORES>(); else wait_vmcnt<WAIT_STEADY>();
-            BDA_STAMP(3);
-            __syncthreads();
-            BDA_STAMP(4);
-            uint32_t tv[PIT], wv[PIW];
-            produce_addr(pt, pk, tv, wv);
-            if constexpr (REG) mma_regular_loads(fw0, ft0, pt, g, 0, tv, wv);
-            else {
-                mma_identity(idf, jc + 16 * (KS - 2), ft0);
-#pragma unroll
-                for (int j = 0; j < LOADS / 2; ++j) issue_load(pt, g, j, tv, wv);
-            }
-            BDA_STAMP(5);
-            if (next_regular) read_w(nb, 0, fw0);
-            read_t(nb, 0, ft0);
-            if constexpr (REG) mma_regular_loads(fw1, ft1, pt, g, LOADS / 2, tv, wv);
-            else {
-                mma_identity(idf, jc + 16 * (KS - 1), ft1);
-#pragma unroll
-                for (int j = LOADS / 2; j < LOADS; ++j) issue_load(pt, g, j, tv, wv);
-            }
-            return;
-        }
-        // k-steps 0 .. KS-2: read the next k-step's fragments, multiply the current ones
-#pragma unroll
-        for (int ks = 0; ks + 1 < KS; ++ks) {
+        for (int ks = 0; ks + 2 < KS; ++ks) {
             if (ks % 2 == 0) {
                 if constexpr (REG) { read_w(sb, ks + 1, fw1); read_t(sb, ks + 1, ft1); mma_regular(fw0, ft0); }
                 else { read_t(sb, ks + 1, ft1); mma_identity(idf, jc + 16 * ks, ft0); }
@@ -478,17 +450,31 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                 else { read_t(sb, ks + 1, ft0); mma_identity(idf, jc + 16 * ks, ft1); }
             }
         }
-        // stage g + 1 must have landed for every wave, and every wave must be done with stage g's
-        // slot (this wave's reads of it are all issued; the barrier's fence completes them)
+        // last read of this stage's slot, then the slot is free once every wave is here
+        if constexpr (REG) read_w(sb, KS - 1, fw1);
+        read_t(sb, KS - 1, ft1);
+        BDA_STAMP(2);
         if (relaxed) wait_vmcnt<WAIT_AFTER_STORES>(); else wait_vmcnt<WAIT_STEADY>();
+        BDA_STAMP(3);
         __syncthreads();
-        produce(pt, pk, g);                   // stage g + NS goes into the slot just freed
+        BDA_STAMP(4);
+        uint32_t tv[PIT], wv[PIW];
+        produce_addr(pt, pk, tv, wv);
+        if constexpr (REG) mma_regular_loads(fw0, ft0, pt, g, 0, tv, wv);
+        else {
+            mma_identity(idf, jc + 16 * (KS - 2), ft0);
+#pragma unroll
+            for (int j = 0; j < LOADS / 2; ++j) issue_load(pt, g, j, tv, wv);
+        }
+        BDA_STAMP(5);
         if (next_regular) read_w(nb, 0, fw0);
         read_t(nb, 0, ft0);
-        if constexpr (REG)
-            mma_regular(fw1, ft1);            // KS is even: the last k-step sits in the second set
-        else
+        if constexpr (REG) mma_regular_loads(fw1, ft1, pt, g, LOADS / 2, tv, wv);
+        else {
             mma_identity(idf, jc + 16 * (KS - 1), ft1);
+#pragma unroll
+            for (int j = LOADS / 2; j < LOADS; ++j) issue_load(pt, g, j, tv, wv);
+        }
     };
 
     BDA_STAMP(0);
