@@ -81,6 +81,17 @@ __device__ __forceinline__ void lds_dma1(u32x4 rsrc, uint32_t lds_addr, uint32_t
         : "s"(lds_addr), "v"(v0), "s"(rsrc)
         : "memory", "m0");
 }
+// the same with a scalar byte offset added to the address (the LDS side is unaffected)
+__device__ __forceinline__ void lds_dma1s(u32x4 rsrc, uint32_t lds_addr, uint32_t v0, uint32_t soff)
+{
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "buffer_load_dwordx4 %1, %2, %3 offen lds\n\t"
+        :
+        : "s"(lds_addr), "v"(v0), "s"(rsrc), "s"(soff)
+        : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void lds_dma(u32x4 rsrc, uint32_t lds_base, const uint32_t (&v)[N])
 {
@@ -278,19 +289,30 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     };
 
     // producer, token tile: load j of wave w fills LDS rows RPI (w PIT + j) + lane/PR, position lane%PR
+    // with the piece (lane%PR) ^ swizzle(row) of that row; weight tile: load j of wave w fills k rows
+    // 2 (w PIW + j) + lane/32, position lane%32 with piece (lane%32) ^ swizzle(k).
+    // Plain vector offset = byte offset of this lane's piece for a stage that starts at column 0 /
+    // row 0; the stage's own offset is uniform and travels in the load's scalar offset, so that a
+    // stage costs no vector arithmetic.  (The range check sees the vector part, which holds the whole
+    // row term: rows past the end of the tensor stay out of range.)
     const uint32_t tok_row_bytes = (uint32_t)(q.lda * 2);
-    const uint32_t p_tok_row_off = (uint32_t)(wave * (RPI * PIT) + lane / PR) * tok_row_bytes;
-    // column of this lane's piece inside the stage; the swizzle sees row bits 0..3, of which bit 3
-    // alternates with j when a load covers only 8 rows
-    int p_tok_k8[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) p_tok_k8[j] = ((lane % PR) ^ tok_swz<SK>((lane / PR + RPI * j) & 15)) * 8;
-    // producer, weight tile: load j of wave w fills k rows 2 (w PIW + j) + lane/32, position lane%32
     const uint32_t wgt_row_bytes = (uint32_t)(q.ldb * 2);
-    const uint32_t p_wgt_row_off = (uint32_t)(wave * (2 * PIW) + (lane >> 5)) * wgt_row_bytes;
-    int p_wgt_c[2];                                   // the swizzle sees k & 3 = (2 j + lane/32) & 3
+    auto tok_k8 = [&](int ln, int j) { return ((ln % PR) ^ tok_swz<SK>((ln / PR + RPI * j) & 15)) * 8; };
+    auto wgt_c = [&](int ln, int j) { return (ln & 31) ^ wgt_swz(2 * j + (ln >> 5)); };
+    // vo_tok[j], vo_wgt[j]: vector offsets of the next stage to request.  Between plain stages they
+    // do not change; a stage that needs per-lane decisions overwrites them and the next plain stage
+    // restores them (vo_is_plain tells which).
+    uint32_t vo_tok[PIT], vo_wgt[PIW];
+    bool vo_is_plain = true;
+    auto plain_offsets = [&](int ln) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) p_wgt_c[j] = (lane & 31) ^ wgt_swz(2 * j + (lane >> 5));
+        for (int j = 0; j < PIT; ++j)
+            vo_tok[j] = (uint32_t)(wave * (RPI * PIT) + ln / PR + RPI * j) * tok_row_bytes + (uint32_t)tok_k8(ln, j & 1) * 2u;
+#pragma unroll
+        for (int j = 0; j < PIW; ++j)
+            vo_wgt[j] = (uint32_t)(wave * (2 * PIW) + (ln >> 5)) * wgt_row_bytes + (uint32_t)wgt_c(ln, j & 1) * 16u;
+    };
+    plain_offsets(lane);
     static_assert((RPI * PIT) % 16 == 0 && (2 * PIW) % 4 == 0, "per-wave row blocks must keep the swizzle phase");
 
     // consumer, token fragments: row = wt*32*TT + ti*32 + l31, piece q = 2 ks + lhi
@@ -310,43 +332,83 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     // ---- producer: stage `k` of tile `t` into LDS slot `g & 3` -------------------------------------
     // Always issues LOADS loads per thread; whatever has nothing to fetch (weights of an identity
     // stage, columns past the group's end, a tile outside the grid) uses an out-of-range offset.
-    auto produce_addr = [&](const StreamTile& t, int k, uint32_t (&tv)[PIT], uint32_t (&wv)[PIW]) {
+    auto general_offsets = [&](const StreamTile& t, int k) {
+        int ln = lane;                        // per-lane terms rebuilt here: this path is rare
+        asm volatile("" : "+v"(ln));
+        plain_offsets(ln);
 #pragma unroll
         for (int j = 0; j < PIT; ++j) {
+            const int k8 = tok_k8(ln, j & 1);
             int col, lim_ok;
             if (k < nk) {
-                const int kk = k * SK + p_tok_k8[j & 1];
+                const int kk = k * SK + k8;
                 col = kk < t.a_off ? kk : kk + q.a_skip;
                 lim_ok = kk < q.K;
             } else {
-                const int jc = t.j_lo + (k - nk) * SK + p_tok_k8[j & 1];
+                const int jc = t.j_lo + (k - nk) * SK + k8;
                 col = t.a_off + jc;
                 lim_ok = jc < q.d_h;
             }
-            tv[j] = lim_ok ? p_tok_row_off + (uint32_t)(RPI * j) * tok_row_bytes + (uint32_t)col * 2u : kBadOffset;
+            vo_tok[j] = lim_ok ? vo_tok[j] + (uint32_t)(col - k8) * 2u : kBadOffset;
         }
-        const uint32_t wbase = k < nk ? p_wgt_row_off + (uint32_t)(k * SK) * wgt_row_bytes : kBadOffset;
 #pragma unroll
         for (int j = 0; j < PIW; ++j)
-            wv[j] = p_wgt_c[j & 1] * 8 < t.cols_left ? wbase + (uint32_t)(2 * j) * wgt_row_bytes + (uint32_t)p_wgt_c[j & 1] * 16u
-                                                      : kBadOffset;
+            vo_wgt[j] = (k < nk && wgt_c(ln, j & 1) * 8 < t.cols_left)
+                            ? vo_wgt[j] + (uint32_t)(k * SK + 2 * j) * wgt_row_bytes : kBadOffset;
     };
-    // load j (0 .. LOADS-1) of a stage whose addresses produce_addr has computed
-    auto issue_load = [&](const StreamTile& t, int g, int j, const uint32_t (&tv)[PIT], const uint32_t (&wv)[PIW]) {
+    // vector offsets for stage k of tile t (uniform branches only)
+    auto prepare_offsets = [&](bool plain, const StreamTile& t, int k) {
+        if (!plain) {
+            general_offsets(t, k);
+            vo_is_plain = false;
+        } else if (!vo_is_plain) {
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            plain_offsets(ln);
+            vo_is_plain = true;
+        }
+    };
+    // A stage whose pieces all exist (full 256 columns, no window edge and no end of K or of the
+    // identity slice inside it) needs no per-lane decisions: uniform offsets only.
+    auto stage_is_plain = [&](const StreamTile& t, int k) -> bool {
+        if (t.cols_left != BN) return false;
+        if (k < nk) {
+            const int k0 = k * SK;
+            return k0 + SK <= q.K && (k0 + SK <= t.a_off || k0 >= t.a_off);
+        }
+        return t.j_lo + (k - nk + 1) * SK <= q.d_h;
+    };
+    // Uniform part of the addresses of stage k of tile t, and which form applies.
+    struct StageOff { bool plain; uint32_t tok_soff, wgt_soff; u32x4 rB; };
+    auto stage_offsets = [&](const StreamTile& t, int k) -> StageOff {
+        StageOff o;
+        o.plain = stage_is_plain(t, k);
+        const int k0 = k * SK;
+        const uint32_t colb = k < nk ? (uint32_t)(k0 < t.a_off ? k0 : k0 + q.a_skip) : (uint32_t)(t.a_off + t.j_lo + (k - nk) * SK);
+        o.tok_soff = o.plain ? colb * 2u : 0u;
+        o.wgt_soff = (o.plain && k < nk) ? (uint32_t)k0 * wgt_row_bytes : 0u;
+        o.rB = t.rB;
+        if (o.plain && k >= nk) o.rB[2] = 0;  // identity stage: the weight slot is filled with zeros
+        return o;
+    };
+    // load j (0 .. LOADS-1) of the stage whose vector offsets prepare_offsets has set
+    auto issue_load = [&](const StreamTile& t, const StageOff& o, int g, int j) {
         if constexpr (!(DBG & 4)) {
             const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
-            if (j < PIT) lds_dma1(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, tv[j < PIT ? j : 0]);
-            else lds_dma1(t.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * (j - PIT), wv[j >= PIT ? j - PIT : 0]);
+            if (j < PIT) {
+                lds_dma1s(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, vo_tok[j < PIT ? j : 0], o.tok_soff);
+            } else {
+                const int jj = j >= PIT ? j - PIT : 0;
+                lds_dma1s(o.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * jj, vo_wgt[jj],
+                          o.plain ? o.wgt_soff + (uint32_t)(2 * jj) * wgt_row_bytes : 0u);
+            }
         }
     };
     auto produce = [&](const StreamTile& t, int k, int g) {
-        uint32_t tv[PIT], wv[PIW];
-        produce_addr(t, k, tv, wv);
-        if constexpr (!(DBG & 4)) {
-            const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
-            lds_dma<PIT>(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT), tv);
-            lds_dma<PIW>(t.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW), wv);
-        }
+        const StageOff o = stage_offsets(t, k);
+        prepare_offsets(o.plain, t, k);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) issue_load(t, o, g, j);
     };
 
     // ---- consumer ---------------------------------------------------------------------------------
@@ -403,8 +465,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     };
     // the same products with this stage's loads j0 .. j0 + n - 1 issued between them, so that the
     // address unit sees a steady trickle instead of every wave's loads at once
-    auto mma_regular_loads = [&](const u32x4 (&fw)[TN], const u32x4 (&ft)[TT], const StreamTile& pt, int g, int j0,
-                                 const uint32_t (&tv)[PIT], const uint32_t (&wv)[PIW]) {
+    auto mma_regular_loads = [&](const u32x4 (&fw)[TN], const u32x4 (&ft)[TT], const StreamTile& pt, const StageOff& so, int g, int j0) {
         constexpr int NL = LOADS / 2, EVERY = (TN * TT) / NL > 0 ? (TN * TT) / NL : 1;
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
@@ -414,7 +475,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                 const int m = ni * TT + ti;
                 if (m % EVERY == EVERY - 1 && m / EVERY < NL) {
                     __builtin_amdgcn_sched_barrier(0);
-                    issue_load(pt, g, j0 + m / EVERY, tv, wv);
+                    issue_load(pt, so, g, j0 + m / EVERY);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -440,6 +501,10 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         if constexpr (!REG) make_idf(idf);
         static_assert(KS % 2 == 0, "fragment sets alternate");
         BDA_STAMP(1);
+        // addresses of the stage requested after this stage's barrier: worked out here, behind the
+        // MFMAs of the first k-steps, so that nothing but the loads themselves follows the barrier
+        const StageOff so = stage_offsets(pt, pk);
+        prepare_offsets(so.plain, pt, pk);
 #pragma unroll
         for (int ks = 0; ks + 2 < KS; ++ks) {
             if (ks % 2 == 0) {
@@ -458,22 +523,20 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         BDA_STAMP(3);
         __syncthreads();
         BDA_STAMP(4);
-        uint32_t tv[PIT], wv[PIW];
-        produce_addr(pt, pk, tv, wv);
-        if constexpr (REG) mma_regular_loads(fw0, ft0, pt, g, 0, tv, wv);
+        if constexpr (REG) mma_regular_loads(fw0, ft0, pt, so, g, 0);
         else {
             mma_identity(idf, jc + 16 * (KS - 2), ft0);
 #pragma unroll
-            for (int j = 0; j < LOADS / 2; ++j) issue_load(pt, g, j, tv, wv);
+            for (int j = 0; j < LOADS / 2; ++j) issue_load(pt, so, g, j);
         }
         BDA_STAMP(5);
         if (next_regular) read_w(nb, 0, fw0);
         read_t(nb, 0, ft0);
-        if constexpr (REG) mma_regular_loads(fw1, ft1, pt, g, LOADS / 2, tv, wv);
+        if constexpr (REG) mma_regular_loads(fw1, ft1, pt, so, g, LOADS / 2);
         else {
             mma_identity(idf, jc + 16 * (KS - 1), ft1);
 #pragma unroll
-            for (int j = LOADS / 2; j < LOADS; ++j) issue_load(pt, g, j, tv, wv);
+            for (int j = LOADS / 2; j < LOADS; ++j) issue_load(pt, so, g, j);
         }
     };
 
