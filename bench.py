@@ -86,11 +86,13 @@ def main() -> int:
     offs = []
     Cs = []
     col = 0
+    t_prep0 = time.perf_counter()
     for Hg in H:                                  # library prepare, first-r basis per group
         Cg, _, off, _ = bda.bda_prepare(w.W[:, col:col + Hg * d_h], d_c, Hg, d_h, mode=bda.BASIS_FIRST)
         Cs.append(Cg)
         offs.append(off)
         col += Hg * d_h
+    t_prep_host = time.perf_counter() - t_prep0
     C_stored, C64 = wl.to_storage(np.hstack(Cs), w.dtype)
     log(f"workload v2lite: T={T} N={N} K={K} max|C|={np.abs(C64).max():.1f}")
     R = max(1, args.rotate)
@@ -207,6 +209,15 @@ def main() -> int:
         t_warm = bench_small(lambda i, s: bda.bda_kv_project(c_bufs[0], d_c, T, d_c, d_h, H, offs, C_d, N,
                                                              o_bufs[0], N, w.dtype, w.dtype, s), args.steps, args.warmup)
         extra["v2lite_T4096_single_buffer"] = {"us": t_warm * 1e6, "tflops": flops / t_warm / 1e12}
+        # basis windows inside the latent (Appendix "Residual-Min with Offset Search": window starts at
+        # multiples of 16): the same launch with other window starts (timing only: C is not re-derived)
+        win = {}
+        for name, o2 in (("last", [K, K]), ("offset_192", [192, 192]), ("offset_208", [208, 208])):
+            t_o = bench_small(lambda i, s, o2=o2: bda.bda_kv_project(c_bufs[i % R], d_c, T, d_c, d_h, H, o2, C_d, N,
+                                                                     o_bufs[i % R], N, w.dtype, w.dtype, s), args.steps, args.warmup)
+            win[name] = {"us": t_o * 1e6, "vs_first": t_o / kernel_s}
+        extra["window_position_cost"] = win
+        log("window position: " + ", ".join(f"{k} {v['us']:.2f} us ({v['vs_first']:.3f}x)" for k, v in win.items()))
         # decode shapes (config 3): rotate over distinct copies of the weights so that each launch
         # streams its 3 MiB of C from HBM, not from cache
         n_w = 96
@@ -265,6 +276,18 @@ def main() -> int:
         extra["lowrank_plain_T8192_f16"] = {"us": t5p * 1e6}
         extra["lowrank_speedup_vs_plain"] = {"measured": t5p / t5, "theoretical": (d_in + d_out) / (d_in + d_out - r5)}
         del x5, U5, C5, o5, V5, h5
+        # preparation itself (off the hot path): host float64 routine vs the GPU routine, first window
+        prep = {"host_v2lite_32_heads_s": t_prep_host}
+        for name, Hh, cdt in (("v2lite_32_heads", 32, wl.F16), ("v3_256_heads", 256, wl.BF16)):
+            Wp = torch.randn((d_c, Hh * d_h), dtype=torch.float32, device="cuda") * 0.02
+            Cp = torch.empty((K, Hh * d_h), dtype=torch.int16, device="cuda")
+            flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+            t_p = bench_small(lambda i, s: bda.bda_prepare_device(Wp, Hh * d_h, wl.F32, d_c, Hh, d_h, 0, Cp, Hh * d_h, cdt, flag, s),
+                              steps=5, warmup=1, graph=False)
+            prep[f"device_{name}_us"] = t_p * 1e6
+            assert int(flag.item()) == 0
+        extra["prepare"] = prep
+        log("prepare: " + ", ".join(f"{k} {v:.3g}" for k, v in prep.items()))
     result["extra"] = extra
 
     # ------------------------------------------------------------------ CPU baseline: the oracle

@@ -100,6 +100,27 @@ int bda_prepare_lowrank(const double* U, const double* V, int d_in, int r, int d
                         double* resid_out);
 
 /*
+ * The same C as bda_prepare, computed on the GPU for an explicit basis window (Algorithm "BD Attention
+ * Preparation (QK)" and Appendix "BD for VO in MHA": C_h = W_h[Bbar,:] W_h[B,:]^{-1}, one workgroup per
+ * head, float64 arithmetic: Gauss-Jordan inverse of the basis block with partial pivoting, then the
+ * product).  The window is chosen by the caller (0 = first, d_c - d_h = last, or the offset that
+ * bda_prepare's residual search returned); companion weights are not handled here.
+ *   W        device, d_c x (H d_h), ld = ldw, element type w_dtype (any bda_dtype).
+ *   C        device, (d_c - d_h) x (H d_h), ld = ldC, element type c_dtype (any bda_dtype); every
+ *            element is rounded once, to nearest even, from the float64 result - ready for
+ *            bda_kv_project.
+ *   singular_head   device int or NULL; the caller zeroes it; after the call has run it holds
+ *            1 + the largest index of a head whose basis block was numerically singular (pivot
+ *            below d_h * 2^-52 * ||W_h[B,:]||_F), or stays 0.  C of such a head is not written.
+ * Asynchronous on `stream`; allocates nothing.  d_h <= 128.  Agrees with bda_prepare to a small
+ * multiple of cond(W_h[B,:]) * 2^-53 (a different elimination order), not bit for bit.
+ * Errors: BDA_EINVAL, BDA_EDTYPE, BDA_EHIP.
+ */
+int bda_prepare_device(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
+                       int basis_offset, void* C, int64_t ldC, bda_dtype c_dtype,
+                       int* singular_head, void* stream);
+
+/*
  * Run-time BD projection, steps 2-3 of Algorithm "BD Attention Inference" (Eq. qk_bd_merge and
  * the V' equation of Appendix "BD for VO in MHA"), all heads of all groups in one launch:
  *

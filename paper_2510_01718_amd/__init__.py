@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT,
     SIDE_NONE, SIDE_Q, SIDE_O,
     BdaError, load, lib_path, exported_symbols,
-    bda_prepare, bda_prepare_lowrank, bda_kv_project, bda_dense_project, bda_lowrank_linear,
+    bda_prepare, bda_prepare_lowrank, bda_prepare_device, bda_kv_project, bda_dense_project, bda_lowrank_linear,
     bda_set_tile_policy, bda_last_error, bda_version,
 )

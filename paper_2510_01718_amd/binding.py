@@ -18,7 +18,7 @@ BDA_F32, BDA_F16, BDA_BF16, BDA_F64 = 0, 1, 2, 3
 BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT = 0, 1, 2, 3, 4
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
-EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_kv_project", "bda_dense_project",
+EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_kv_project", "bda_dense_project",
            "bda_lowrank_linear", "bda_set_tile_policy", "bda_last_error", "bda_version")
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -54,6 +54,8 @@ def load():
                                 c_int, dp, dp, ip, dp]
     lib.bda_prepare_lowrank.restype = c_int
     lib.bda_prepare_lowrank.argtypes = [dp, dp, c_int, c_int, c_int, c_int, c_int, dp, dp, ip, dp]
+    lib.bda_prepare_device.restype = c_int
+    lib.bda_prepare_device.argtypes = [vp, i64, c_int, c_int, c_int, c_int, c_int, vp, i64, c_int, vp, vp]
     lib.bda_kv_project.restype = c_int
     lib.bda_kv_project.argtypes = [vp, i64, i64, c_int, c_int, c_int, ip, ip, vp, i64, vp, i64,
                                    c_int, c_int, vp]
@@ -169,6 +171,13 @@ def bda_kv_project(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],
     _check(lib.bda_kv_project(_ptr(c), ldc, T, d_c, d_h, G, _int_array(H), _int_array(basis_offset),
                               _ptr(C), ldC, _ptr(out), ld_out, dtype,
                               dtype if out_dtype is None else out_dtype, stream or None))
+
+
+def bda_prepare_device(W, ldw: int, w_dtype: int, d_c: int, H: int, d_h: int, basis_offset: int,
+                       C, ldC: int, c_dtype: int, singular_head=None, stream: int = 0) -> None:
+    lib = load()
+    _check(lib.bda_prepare_device(_ptr(W), ldw, w_dtype, d_c, H, d_h, basis_offset, _ptr(C), ldC, c_dtype,
+                                  _ptr(singular_head), stream or None))
 
 
 def bda_dense_project(c, ldc: int, T: int, d_c: int, W, ldW: int, N: int, out, ld_out: int,

@@ -296,3 +296,145 @@ def test_library_prepare_then_project_scores():
         dense = Q[:, s] @ K[:, s].T
         nmse = np.sum((ref - dense) ** 2) / np.sum(dense ** 2)
         assert nmse < 1e-2, nmse     # fp16 storage of C only; exact in float64 (oracle pins)
+
+
+def _gpu_dense(x64, W64, dtype, out_dtype):
+    """out = x W on the GPU (bda_dense_project) from float64 arrays rounded to `dtype`."""
+    xs, _ = wl.to_storage(x64, dtype)
+    Ws, _ = wl.to_storage(W64, dtype)
+    T, K = x64.shape
+    N = W64.shape[1]
+    x_d, W_d = gh.to_device(xs, dtype), gh.to_device(Ws, dtype)
+    out_d = gh.new_out(T, N, out_dtype)
+    bda.bda_dense_project(x_d, K, T, K, W_d, N, N, out_d, N, dtype, out_dtype, stream=gh.stream())
+    torch.cuda.synchronize()
+    return gh.to_host64(out_d, out_dtype)
+
+
+def _softmax_attention(Q, K, V, n, d_h):
+    out = np.empty_like(V)
+    for h in range(n):
+        s = slice(h * d_h, (h + 1) * d_h)
+        a = Q[:, s] @ K[:, s].T / np.sqrt(d_h)
+        a = np.exp(a - a.max(axis=1, keepdims=True))
+        out[:, s] = (a / a.sum(axis=1, keepdims=True)) @ V[:, s]
+    return out
+
+
+def test_full_bda_layer_matches_mha():
+    """All six steps of Algorithm "BD Attention Inference" for one MHA layer: Q' = X B_qk (GPU dense
+    GEMM), K' and V' (GPU BD projection, both groups in one launch), softmax attention per head (host,
+    float64, from the GPU's Q', K', V'), Y = O' B_vo (GPU dense GEMM).  Checked against the same
+    steps in float64 on the same stored weights, and against plain MHA (Algorithm "MHA Inference")
+    on the original weights, from which it may differ only by the storage rounding of the BD weights."""
+    rng = np.random.default_rng(41)
+    T, d, n, d_h = 200, 256, 4, 64
+    X = rng.standard_normal((T, d))
+    Wq, Wk, Wv = (rng.standard_normal((d, n * d_h)) / np.sqrt(d) for _ in range(3))
+    Wo = rng.standard_normal((n * d_h, d)) / np.sqrt(n * d_h)
+    dt = wl.F16
+    Cqk, Bqk, off_k, _ = bda.bda_prepare(Wk, d, n, d_h, Wq, bda.SIDE_Q, bda.BASIS_RESIDUAL_MIN, 0, bda.BDA_F16)
+    Cvo, Bvo, off_v, _ = bda.bda_prepare(Wv, d, n, d_h, Wo, bda.SIDE_O, bda.BASIS_RESIDUAL_MIN, 0, bda.BDA_F16)
+    Xs, X64 = wl.to_storage(X, dt)
+    Cs, C64 = wl.to_storage(np.hstack([Cqk, Cvo]), dt)
+    _, Bqk64 = wl.to_storage(Bqk, dt)
+    _, Bvo64 = wl.to_storage(Bvo, dt)
+    # GPU
+    Qp = _gpu_dense(X64, Bqk64, dt, wl.F32)
+    KV, _ = gh.kv_project(Xs, Cs, d, d_h, [n, n], [off_k, off_v], dt, out_dtype=wl.F32)
+    Kp, Vp = KV[:, :n * d_h], KV[:, n * d_h:]
+    Op = _softmax_attention(Qp, Kp, Vp, n, d_h)
+    Y = _gpu_dense(Op, Bvo64, dt, wl.F32)
+    # the same steps in float64 on the same stored weights
+    Qp_r = oracle.dense_project(X64, Bqk64)
+    KV_r = oracle.kv_project(X64, C64, d_h, [n, n], [off_k, off_v])
+    Op_r = _softmax_attention(Qp_r, KV_r[:, :n * d_h], KV_r[:, n * d_h:], n, d_h)
+    assert_parity(Qp, Qp_r, d_h, dt, wl.F32, "Q'")
+    assert_parity(KV, KV_r, d_h, dt, wl.F32, "K', V'")
+    assert_parity(Op, Op_r, d_h, dt, wl.F32, "O'")
+    # step 6 on the GPU against float64 on the very same stored O' (O' is rounded to the storage type
+    # on its way into the GEMM; Y cancels heavily, so two roundings of slightly different O' would
+    # not be comparable at the element level)
+    _, Op16 = wl.to_storage(Op, dt)
+    assert_parity(Y, oracle.dense_project(Op16, Bvo64), d, dt, wl.F32, "Y")
+    # plain MHA on the original weights: the whole GPU pipeline differs from it only by storage rounding
+    Y_mha = _softmax_attention(X64 @ Wq, X64 @ Wk, X64 @ Wv, n, d_h) @ Wo
+    for name, y in (("GPU", Y), ("float64 BDA", oracle.dense_project(wl.to_storage(Op_r, dt)[1], Bvo64))):
+        nmse = np.sum((y - Y_mha) ** 2) / np.sum(Y_mha ** 2)
+        assert nmse < 1e-3, (name, nmse)
+
+
+# --------------------------------------------------------------------------------- GPU preparation
+def _prepare_device(W_in, w_dtype, d_c, H, d_h, off, c_dtype):
+    if w_dtype == wl.F64:
+        W_d = torch.from_numpy(np.ascontiguousarray(W_in, dtype=np.float64)).cuda()
+    else:
+        W_d = gh.to_device(wl.to_storage(W_in, w_dtype)[0], w_dtype)
+    N = H * d_h
+    tdt = {wl.F64: torch.float64, wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.int16}[c_dtype]
+    C_d = torch.full((d_c - d_h, N), -7, dtype=tdt, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    bda.bda_prepare_device(W_d, N, w_dtype, d_c, H, d_h, off, C_d, N, c_dtype, flag, gh.stream())
+    torch.cuda.synchronize()
+    if c_dtype == wl.F64:
+        C = C_d.cpu().numpy()
+    else:
+        C = gh.to_host64(C_d, c_dtype)
+    return C, int(flag.item()), C_d
+
+
+@pytest.mark.parametrize("d_c,H,d_h,off", [(512, 4, 128, 0), (512, 3, 128, 384), (512, 2, 128, 208),
+                                           (256, 5, 64, 64), (96, 3, 32, 16), (64, 2, 16, 0)])
+def test_prepare_device_matches_oracle(d_c, H, d_h, off):
+    """GPU preparation (Gauss-Jordan inverse in float64) against the oracle's solve, same window.
+    The two eliminate in different orders, so they agree to a multiple of cond * 2^-53, not bit for
+    bit; the tolerance below is 1e-9 of the largest coefficient."""
+    w = wl.custom_kv_workload("prep", T=1, d_c=d_c, d_h=d_h, H=[H], std=0.02, rms_norm=False, dtype=wl.F32, seed=50 + d_h)
+    C_ref, _, off_ref, _ = oracle.prepare(w.W, d_c, H, d_h, mode=oracle.EXPLICIT, explicit_offset=off)
+    assert off_ref == off
+    C, flag, _ = _prepare_device(w.W, wl.F64, d_c, H, d_h, off, wl.F64)
+    assert flag == 0
+    assert np.max(np.abs(C - C_ref)) <= 1e-9 * np.max(np.abs(C_ref))
+    # the transformed weight has the identity in its window rows (the paper's defining property)
+    for h in range(H):
+        A = w.W[off:off + d_h, h * d_h:(h + 1) * d_h]
+        rest = np.concatenate([np.arange(0, off), np.arange(off + d_h, d_c)])
+        assert np.allclose(C[:, h * d_h:(h + 1) * d_h] @ A, w.W[rest, h * d_h:(h + 1) * d_h], rtol=0, atol=1e-10)
+
+
+@pytest.mark.parametrize("w_dtype", [wl.F16, wl.BF16, wl.F32])
+@pytest.mark.parametrize("c_dtype", [wl.F16, wl.BF16, wl.F32])
+def test_prepare_device_storage_types(w_dtype, c_dtype):
+    """Inputs in a storage type are taken at their stored value; outputs are the float64 result rounded
+    once: equal to rounding the float64 output of the same call, element for element."""
+    d_c, H, d_h, off = 256, 3, 64, 0
+    w = wl.custom_kv_workload("prep", T=1, d_c=d_c, d_h=d_h, H=[H], std=0.02, rms_norm=False, dtype=wl.F32, seed=61)
+    _, W64 = wl.to_storage(w.W, w_dtype)
+    C64, flag, _ = _prepare_device(w.W, w_dtype, d_c, H, d_h, off, wl.F64)
+    assert flag == 0
+    C_ref, _, _, _ = oracle.prepare(W64, d_c, H, d_h, mode=oracle.EXPLICIT, explicit_offset=off)
+    assert np.max(np.abs(C64 - C_ref)) <= 1e-9 * np.max(np.abs(C_ref))
+    Cs, flag, _ = _prepare_device(w.W, w_dtype, d_c, H, d_h, off, c_dtype)
+    assert flag == 0
+    _, want = wl.to_storage(C64, c_dtype)
+    assert np.array_equal(Cs, want)
+
+
+def test_prepare_device_flags_singular_head_and_feeds_projection():
+    d_c, H, d_h = 128, 3, 32
+    w = wl.custom_kv_workload("prep", T=70, d_c=d_c, d_h=d_h, H=[H], std=0.125, rms_norm=False, dtype=wl.F16, seed=62)
+    Wb = w.W.copy()
+    Wb[5, d_h:2 * d_h] = Wb[9, d_h:2 * d_h]          # head 1: two equal rows inside the first window
+    _, flag, C_d = _prepare_device(Wb, wl.F64, d_c, H, d_h, 0, wl.F64)
+    assert flag == 2
+    # heads that are fine are still written; the singular one keeps the caller's fill
+    assert np.all(C_d.cpu().numpy()[:, d_h:2 * d_h] == -7)
+    # regular input: prepare on the GPU in the storage type, project, compare with the oracle on that C
+    Cs, flag, C_d = _prepare_device(w.W, wl.F64, d_c, H, d_h, 0, wl.F16)
+    assert flag == 0
+    c_d = gh.to_device(w.c_stored, wl.F16)
+    out_d = gh.new_out(w.T, H * d_h, wl.F16)
+    bda.bda_kv_project(c_d, d_c, w.T, d_c, d_h, [H], [0], C_d, H * d_h, out_d, H * d_h, wl.F16, wl.F16, gh.stream())
+    torch.cuda.synchronize()
+    ref = oracle.kv_project(w.c, Cs, d_h, [H], [0])
+    assert_parity(gh.to_host64(out_d, wl.F16), ref, d_h, wl.F16, wl.F16, "prepare_device -> kv_project")

@@ -163,6 +163,13 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     # T = 0 is a successful no-op even with NULL buffers
     assert lib.bda_kv_project(None, 64, 0, 64, 16, 1, H, off, None, 32, None, 32, 1, 1, None) == 0
     assert lib.bda_last_error() == b""
+    # GPU preparation: NULL, window out of range, head too wide for the LDS-resident inverse, bad dtype
+    assert lib.bda_prepare_device(None, 32, 3, 64, 2, 16, 0, fake, 32, 1, None, None) == -1
+    assert lib.bda_prepare_device(fake, 32, 3, 64, 2, 16, 49, fake, 32, 1, None, None) == -1
+    assert b"basis_offset" in lib.bda_last_error()
+    assert lib.bda_prepare_device(fake, 512, 3, 1024, 2, 256, 0, fake, 512, 1, None, None) == -1
+    assert lib.bda_prepare_device(fake, 32, 7, 64, 2, 16, 0, fake, 32, 1, None, None) == -3
+    assert lib.bda_prepare_device(fake, 16, 3, 64, 2, 16, 0, fake, 32, 1, None, None) == -1
     assert lib.bda_dense_project(fake, 64, 4, 64, fake, 8, 32, fake, 32, 1, 1, None) == -1
     assert lib.bda_lowrank_linear(fake, 64, 4, 64, 8, 40, 3, fake, fake, fake, 40, 1, None) == -1
     assert lib.bda_set_tile_policy(7) == -1
