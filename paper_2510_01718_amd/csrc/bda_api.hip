@@ -8,6 +8,7 @@
 #include "bda_gemm_kernels.hpp"
 #include "bda_decode.hpp"
 #include "bda_gemm_stream.hpp"
+#include "bda_gemm_plain.hpp"
 #include "bda_internal.h"
 
 namespace bda {
@@ -56,13 +57,16 @@ int launch_mfma(GemmArgs& a, hipStream_t st)
 // Streaming kernel: 8 waves, stages of 64, two LDS stages (+ 4 KiB of epilogue staging per wave).
 constexpr int kStreamSK = 64, kStreamNS = 2;
 
+// Streaming kernel; `plain` selects its lean variant (every stage of every tile free of per-lane
+// decisions: see bda_gemm_plain.hpp).
 template <typename X, typename OutT>
-int launch_stream(GemmArgs& a, hipStream_t st)
+int launch_stream(GemmArgs& a, bool plain, hipStream_t st)
 {
-    static std::once_flag once;
+    static std::once_flag once, once_plain;
     constexpr int lds = kStreamNS * (256 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
     auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS, 0>;
-    if (int rc = set_max_lds(kern, lds, once)) return rc;
+    auto kern_plain = gemm_plain_kernel<X, OutT, 0>;
+    if (int rc = plain ? set_max_lds(kern_plain, lds, once_plain) : set_max_lds(kern, lds, once)) return rc;
     a.n_super_m = (a.m_tiles + a.sm - 1) / a.sm;
     a.n_super_n = (a.n_tiles + a.sn - 1) / a.sn;
     a.sn_shift = 0;
@@ -78,7 +82,8 @@ int launch_stream(GemmArgs& a, hipStream_t st)
             a.xcd_count[x] = (int)std::min<int64_t>(a.rounds, total - first);
         }
     }
-    hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
+    if (plain) hipLaunchKernelGGL(kern_plain, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
+    else hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
@@ -165,7 +170,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         int64_t nt256 = 0;
         for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
         const int policy = g_tile_policy.load();
-        const bool big = policy == 2 || (policy == 0 && mt256 * nt256 >= 192);
+        const bool big = policy == 2 || policy == 3 || (policy == 0 && mt256 * nt256 >= 192);
         if (big) {
             build_tiles(a, G, group_cols, 256, 256);
             choose_super(a, kSlotsPerXcd);
@@ -179,8 +184,12 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         bool stream = big && (a.K + kStreamSK - 1) / kStreamSK + a.n_stage_id >= kStreamNS;
         for (int g = 0; g < G; ++g) stream = stream && group_cols[g] < (1 << 24);   // exact x % d_h by multiplication
         stream = stream && a.d_h < (1 << 16);
+        // the lean variant: nothing in any stage depends on the lane (see bda_gemm_plain.hpp)
+        bool plain = stream && kStreamSK == 64 && kStreamNS == 2 && a.K % 64 == 0 && (!a.ident || a.d_h % 64 == 0)
+                     && g_tile_policy.load() != 3;
+        for (int g = 0; g < G; ++g) plain = plain && group_cols[g] % 256 == 0 && a.a_off[g] % 64 == 0;
 #define BDA_LAUNCH(X, O)                                      \
-    return stream ? launch_stream<X, O>(a, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
+    return stream ? launch_stream<X, O>(a, plain, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
         if (dtype == BDA_F16 && out_dtype == BDA_F16) { BDA_LAUNCH(F16, uint16_t); }
         if (dtype == BDA_F16 && out_dtype == BDA_F32) { BDA_LAUNCH(F16, float); }
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) { BDA_LAUNCH(BF16, uint16_t); }
@@ -214,7 +223,7 @@ using namespace bda;
 extern "C" int bda_set_tile_policy(int policy)
 {
     clear_error();
-    if (policy < 0 || policy > 2) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0, 1 or 2");
+    if (policy < 0 || policy > 3) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0 .. 3");
     return g_tile_policy.exchange(policy);
 }
 
