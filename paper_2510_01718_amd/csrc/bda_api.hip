@@ -123,17 +123,26 @@ void build_tiles(GemmArgs& a, int G, const int64_t* group_cols, int bt, int bn)
     a.m_tiles = (int)((a.M + bt - 1) / bt);
 }
 
-// Shape of the block of tiles one die works on at a time: sm x sn = slots, as square as the tile
-// grid allows, so that the die's L2 holds few distinct token and weight tiles.
-void choose_super(GemmArgs& a, int slots)
+// Shape of the block of tiles one die works on at a time: sm x sn = slots (workgroups per die), as
+// square as the tile grid allows, so that the die's L2 holds few distinct token and weight tiles.
+// A small tile grid gets fewer slots, so that there are at least as many super-tiles as dies and
+// every die (and its share of the memory channels) takes part.
+void choose_super(GemmArgs& a, int max_slots)
 {
     auto pow2ceil = [](int v) { int p = 1; while (p < v) p *= 2; return p; };
     const int mcap = pow2ceil(a.m_tiles), ncap = pow2ceil(a.n_tiles);
-    int sm = slots >= 64 ? 8 : 4;
-    while (sm > 1 && sm > mcap) sm /= 2;                       // no slots for missing token tiles
-    while (slots / sm > ncap && sm * 2 <= mcap) sm *= 2;       // nor for missing column tiles
-    a.sm = sm;
-    a.sn = slots / sm;
+    for (int slots = max_slots;; slots /= 2) {
+        int sm = slots >= 64 ? 8 : slots >= 16 ? 4 : slots >= 4 ? 2 : 1;
+        while (sm > 1 && sm > mcap) sm /= 2;                       // no slots for missing token tiles
+        while (slots / sm > ncap && sm * 2 <= mcap) sm *= 2;       // nor for missing column tiles
+        const int sn = slots / sm;
+        const int64_t n_super = (int64_t)((a.m_tiles + sm - 1) / sm) * ((a.n_tiles + sn - 1) / sn);
+        if (n_super >= kNumXcd || slots == 1) {
+            a.sm = sm;
+            a.sn = sn;
+            return;
+        }
+    }
 }
 
 // Common launcher.  a.A/B/D, lda/ldb/ldd, M, K, d_h, a_skip, ident and a_off[] are set by the caller.
@@ -170,7 +179,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         int64_t nt256 = 0;
         for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
         const int policy = g_tile_policy.load();
-        const bool big = policy == 2 || policy == 3 || (policy == 0 && mt256 * nt256 >= 192);
+        const bool big = policy == 2 || policy == 3 || (policy == 0 && mt256 * nt256 >= 96);   // measured crossover
         if (big) {
             build_tiles(a, G, group_cols, 256, 256);
             choose_super(a, kSlotsPerXcd);
