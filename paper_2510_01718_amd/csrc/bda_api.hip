@@ -195,6 +195,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         stream = stream && a.d_h < (1 << 16);
         // the lean variant: nothing in any stage depends on the lane (see bda_gemm_plain.hpp)
         bool plain = stream && kStreamSK == 64 && kStreamNS == 2 && a.K % 64 == 0 && (!a.ident || a.d_h % 64 == 0)
+                     && a.K / 64 + a.n_stage_id >= 3 && a.K >= 64
                      && g_tile_policy.load() != 3;
         for (int g = 0; g < G; ++g) plain = plain && group_cols[g] % 256 == 0 && a.a_off[g] % 64 == 0;
 #define BDA_LAUNCH(X, O)                                      \

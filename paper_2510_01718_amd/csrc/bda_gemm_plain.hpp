@@ -160,7 +160,8 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
         vo_wgt[j] = (uint32_t)(wave * (2 * PIW) + (lane >> 5)) * wgt_row_bytes + (uint32_t)(((lane & 31) ^ wgt_swz(2 * j + (lane >> 5))) * 16);
-    const uint32_t wave_lds = (uint32_t)wave * 4096u;             // this wave's 4 KiB of each half slot
+    const uint32_t wave_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem
+                              + (uint32_t)wave * 4096u;           // this wave's 4 KiB of each half slot (absolute LDS address)
     const uint32_t wgt_step = 2u * wgt_row_bytes;                  // rows between a wave's weight loads
 
     // Requests stage k of tile t into the slot at byte `slot_b`; loads j0 .. j0+3 (0: tokens, 4: weights).
@@ -207,9 +208,13 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
     u32x4 fw0[TN], ft0[TT], fw1[TN], ft1[TT];
 
-    // LDS addresses of this lane's fragments in the slot being read; flipped to the other slot by
-    // XOR with the slot size after a stage's last read
-    uint32_t a_tok = (uint32_t)((wt * (32 * TT) + l31) * RB + ((lhi ^ tok_swz<SK>(l31 & 15)) << 4));
+    // LDS addresses of this lane's fragments in the slot being read; moved to the other slot (plus or
+    // minus the slot size) after a stage's last read
+    // (absolute LDS addresses: the start of the dynamic LDS block is folded in here once)
+    typedef __attribute__((address_space(3))) unsigned char* lds_u8;
+    typedef __attribute__((address_space(3))) const u32x4* lds_u32x4;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8)smem;
+    uint32_t a_tok = lds0 + (uint32_t)((wt * (32 * TT) + l31) * RB + ((lhi ^ tok_swz<SK>(l31 & 15)) << 4));
     uint32_t a_wgt[TN];
     {
         const int c_s = lane & 15, c_gq = lane >> 4;
@@ -217,19 +222,21 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         for (int ni = 0; ni < TN; ++ni) {
             const int col = wn * (32 * TN) + ni * 32 + 16 * (c_gq & 1) + 4 * (c_s & 3);
             const int piece = (col >> 3) ^ wgt_swz(c_s >> 2);
-            a_wgt[ni] = (uint32_t)(TOK_BYTES + (8 * lhi + (c_s >> 2)) * 512 + (piece << 4) + ((col & 4) << 1));
+            a_wgt[ni] = lds0 + (uint32_t)(TOK_BYTES + (8 * lhi + (c_s >> 2)) * 512 + (piece << 4) + ((col & 4) << 1));
         }
     }
+    uint32_t flip = (uint32_t)STAGE_BYTES;     // uniform: +slot size, then -slot size, ...
     auto flip_slot = [&]() {
-        a_tok ^= (uint32_t)STAGE_BYTES;
+        a_tok += flip;
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni) a_wgt[ni] ^= (uint32_t)STAGE_BYTES;
+        for (int ni = 0; ni < TN; ++ni) a_wgt[ni] += flip;
+        flip = 0u - flip;
     };
     auto read_w = [&](int ks, u32x4 (&fw)[TN]) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + a_wgt[ni] + (16 * ks) * 512));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + a_wgt[ni] + (16 * ks + 4) * 512));
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(uintptr_t)(a_wgt[ni] + (16 * ks) * 512));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(uintptr_t)(a_wgt[ni] + (16 * ks + 4) * 512));
             const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
             fw[ni] = (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
         }
@@ -237,7 +244,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     auto read_t = [&](int ks, u32x4 (&ft)[TT]) {
         const uint32_t a = a_tok ^ (uint32_t)(ks << 5);
 #pragma unroll
-        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(smem + a + ti * (32 * RB));
+        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(lds_u32x4)(uintptr_t)(a + ti * (32 * RB));
     };
     int rel_blk[TN] = {};
     auto mma_identity = [&](const u32x4 (&idf)[2], int col0, const u32x4 (&ft)[TT]) {
@@ -262,8 +269,9 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     // into the same slot once every wave has read it.  The eight MFMAs of each of the last two k-steps
     // carry four loads between them.
     uint32_t slot_b = 0;
-    auto stage = [&](auto regular, const StreamTile& cur, int kc, const StreamTile& pt, int pk, bool relaxed) {
+    auto stage = [&](auto regular, auto first_of_tile, const StreamTile& cur, int kc, const StreamTile& pt, int pk, bool relaxed) {
         constexpr bool REG = decltype(regular)::value;
+        constexpr bool FIRST = decltype(first_of_tile)::value;   // only then may result stores be in flight
         const bool next_regular = kc + 1 < nk || kc + 1 == S;
         const int jc = cur.j_lo + (kc - nk) * SK;
         u32x4 idf[2];
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         if (pk >= nk) rW[2] = 0;              // identity stage: the weight half of the slot is filled with zeros
         const uint32_t ws = pk < nk ? (uint32_t)(pk * SK) * wgt_row_bytes : 0u;
         BDA_STAMP(2);
-        if (relaxed) wait_vmcnt<STORES>(); else wait_vmcnt<0>();
+        if (FIRST && relaxed) wait_vmcnt<STORES>(); else wait_vmcnt<0>();
         BDA_STAMP(3);
         __syncthreads();
         BDA_STAMP(4);
@@ -368,15 +376,17 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             if (rel_blk[ni] >= q.d_h) rel_blk[ni] -= q.d_h;
         }
         const bool after_tile = round > 0;
-        int kc = 0;
+        // stage 0 of the tile apart (host contract: S >= 3, so it requests stage 2 of the same tile)
+        stage(REGULAR, std::true_type{}, cur, 0, cur, 2, after_tile);
+        int kc = 1;
 #pragma unroll 1
-        for (; kc < r_same; ++kc) stage(REGULAR, cur, kc, cur, kc + 2, after_tile && kc < 1);
+        for (; kc < r_same; ++kc) stage(REGULAR, std::false_type{}, cur, kc, cur, kc + 2, false);
 #pragma unroll 1
-        for (; kc < nk; ++kc) stage(REGULAR, cur, kc, nxt, kc - split, after_tile && kc < 1);
+        for (; kc < nk; ++kc) stage(REGULAR, std::false_type{}, cur, kc, nxt, kc - split, false);
 #pragma unroll 1
-        for (; kc < i_same; ++kc) stage(IDENTITY, cur, kc, cur, kc + 2, after_tile && kc < 1);
+        for (; kc < i_same; ++kc) stage(IDENTITY, std::false_type{}, cur, kc, cur, kc + 2, false);
 #pragma unroll 1
-        for (; kc < S; ++kc) stage(IDENTITY, cur, kc, nxt, kc - split, after_tile && kc < 1);
+        for (; kc < S; ++kc) stage(IDENTITY, std::false_type{}, cur, kc, nxt, kc - split, false);
 
         BDA_STAMP(6);
         // ---- epilogue ---------------------------------------------------------------------------
