@@ -167,7 +167,8 @@ int bda_lowrank_linear(const void* x, int64_t ldx, int64_t T, int d_in, int r, i
 
 /*
  * Tuning / testing hook: which MFMA tile the fp16/bf16 kernels use.  0 = automatic (default: the
- * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256.
+ * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256,
+ * 3 = 256 x 256 with the general streaming kernel even where its lean variant would apply.
  * Process-wide; returns the previous policy, or BDA_EINVAL.  Results do not depend on it beyond
  * float32 summation order inside a tile (none: the order over k is the same for every tile shape).
  */

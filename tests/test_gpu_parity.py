@@ -79,6 +79,38 @@ def test_kv_medium_ragged(policy, dtype, offs):
     _run_kv_case(w, offs, policy=policy)
 
 
+@pytest.mark.parametrize("policy", [2, 3])
+@pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.F16, wl.F32)])
+@pytest.mark.parametrize("offs", [[0, 0], [384, 384], [64, 192]])
+def test_kv_lean_and_general_streaming_kernels(policy, dtype, out_dtype, offs):
+    """Full 256-column tiles and windows on multiples of 64: policy 2 runs the lean streaming kernel,
+    policy 3 forces the general one on the same launch; 700 tokens = three token tiles per workgroup
+    column, the last one ragged."""
+    w = wl.custom_kv_workload("lean", T=700, d_c=512, d_h=128, H=[4, 2], std=0.02, rms_norm=True,
+                              dtype=dtype, seed=12)
+    _run_kv_case(w, offs, out_dtype=out_dtype, policy=policy)
+
+
+@pytest.mark.parametrize("policy", [2, 3])
+def test_dense_many_stages_streaming(policy):
+    """A long contraction (K = 1024: 16 stages per tile, no identity slice) through both streaming kernels."""
+    rng = np.random.default_rng(13)
+    T, K, N = 520, 1024, 512
+    x = rng.standard_normal((T, K))
+    W = rng.standard_normal((K, N)) * 0.05
+    xs, x64 = wl.to_storage(x, wl.F16)
+    Ws, W64 = wl.to_storage(W, wl.F16)
+    x_d, W_d = gh.to_device(xs, wl.F16), gh.to_device(Ws, wl.F16)
+    out_d = gh.new_out(T, N, wl.F16)
+    bda.bda_set_tile_policy(policy)
+    try:
+        bda.bda_dense_project(x_d, K, T, K, W_d, N, N, out_d, N, wl.F16, stream=gh.stream())
+    finally:
+        bda.bda_set_tile_policy(0)
+    torch.cuda.synchronize()
+    assert_parity(gh.to_host64(out_d, wl.F16), oracle.dense_project(x64, W64), N, wl.F16, wl.F16, "dense K=1024")
+
+
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
 def test_kv_fp32_output_meets_plain_tolerance(dtype):
     w = wl.custom_kv_workload("medium32", T=200, d_c=512, d_h=128, H=[2, 2], std=0.02, rms_norm=True,
