@@ -14,6 +14,8 @@ Two layers, both float64:
   (Eq. qk_bd_single) and the row-first BD of W_v^h W_o^h (Appendix "BD for VO in MHA"), and the
   run-time operators (`kv_project`, `dense_project`, `lowrank_linear`), which are C loops over the
   defining formulas in `bd_project.c`.
+* The gradients of the K/V projection for BDA training (`kv_project_backward`): the chain rule
+  applied head by head to steps 2-3 of Algorithm "BD Attention Inference", with numpy products.
 
 Readings of the paper that the text leaves open are listed where they are applied.
 All pins of this oracle live in tests/test_oracle_*.py; no function here is "parity unpinned".
@@ -402,3 +404,38 @@ def lowrank_linear(x: np.ndarray, Uprime: np.ndarray, C: np.ndarray,
         _load().oracle_lowrank_linear(_dptr(x), d_in, T, d_in, r, d_out, int(basis_offset),
                                       _dptr(Uprime), _dptr(C), _dptr(out), d_out, _dptr(hbuf))
     return out
+
+
+# ------------------------------------------------------------------------------------------------
+# training: gradients of the K/V projection
+# ------------------------------------------------------------------------------------------------
+def kv_project_backward(c: np.ndarray, d_out: np.ndarray, C: np.ndarray, d_h: int,
+                        H: Sequence[int], basis_offset: Sequence[int]
+                        ) -> Tuple[np.ndarray, np.ndarray]:
+    """Gradients of a loss through `kv_project` (Section "BDA Training Evaluation": C is a learnable
+    parameter and gradients flow through the forward of Algorithm "BD Attention Inference").
+
+    With out_h = c[:, B] + c[:, Bbar] C_h (steps 2-3) and d_out = dL/d out, head by head:
+        dL/dC_h        = c[:, Bbar]^T d_out_h
+        dL/dc[:, Bbar] += d_out_h C_h^T
+        dL/dc[:, B]    += d_out_h            (the repeated basis slice: one copy per head)
+    Returns (d_c, d_C) in float64, shaped like c and C."""
+    c, d_out, C = _c64(c), _c64(d_out), _c64(C)
+    T, d_c = c.shape
+    N = int(sum(H)) * d_h
+    assert C.shape == (d_c - d_h, N) and d_out.shape == (T, N)
+    grad_c = np.zeros((T, d_c), dtype=np.float64)
+    grad_C = np.zeros((d_c - d_h, N), dtype=np.float64)
+    col = 0
+    for n_heads, off in zip(H, basis_offset):
+        assert 0 <= off <= d_c - d_h
+        bbar = window_complement(d_c, d_h, int(off))
+        c_bbar = c[:, bbar]
+        for _ in range(int(n_heads)):
+            head = slice(col, col + d_h)
+            g_h = d_out[:, head]
+            grad_C[:, head] = c_bbar.T @ g_h
+            grad_c[:, bbar] += g_h @ C[:, head].T
+            grad_c[:, off:off + d_h] += g_h
+            col += d_h
+    return grad_c, grad_C
