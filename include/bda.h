@@ -166,9 +166,38 @@ int bda_lowrank_linear(const void* x, int64_t ldx, int64_t T, int d_in, int r, i
                        void* out, int64_t ld_out, bda_dtype dtype, void* stream);
 
 /*
+ * Gradients of bda_kv_project for BDA training (Section "BDA Training Evaluation": C replaces the
+ * projection as the learnable parameter and gradients flow through steps 2-3 of Algorithm "BD
+ * Attention Inference").  With d_out = dL/d out (T x N):
+ *
+ *     grad_c[t, l] = sum_g ( [l in window g] sum_h d_out[t, col0_g + h d_h + l - off_g]
+ *                          + [l outside it]   sum_{n in group g} d_out[t, n] C[rank_g(l), n] )
+ *     grad_C[i, n] = sum_t c[t, Bbar_g(i)] d_out[t, n]          (g = the group that owns column n)
+ *
+ *   c, C, G, H, basis_offset, T, d_c, d_h   as in bda_kv_project (element type `dtype`).
+ *   d_out    device, T x N, ld = ld_dout, element type `dtype`.
+ *   grad_c   device or NULL (skip; then C may be NULL), T x d_c, ld = ld_gc.
+ *   grad_C   device or NULL (skip; then c may be NULL), (d_c - d_h) x N, ld = ld_gC.
+ *            Both are OVERWRITTEN (not accumulated into), element type `grad_dtype` (= dtype, or
+ *            BDA_F32).  With T = 0, grad_C is written with zeros and grad_c is not touched.
+ * Each gradient is one launch on `stream`; products are accumulated in float32 (fp16/bf16 inputs use
+ * MFMA; the head sum on the window is part of the same accumulation) and rounded once when stored.
+ * The MFMA path needs 16-byte aligned pointers, ld's, d_c and basis offsets that are multiples of 8
+ * and d_h a multiple of 32; anything else (and BDA_F32 inputs) runs slower general kernels with
+ * the same result contract.  Gradients must not overlap the inputs or each other.
+ * Errors: BDA_EINVAL, BDA_EDTYPE, BDA_EHIP.
+ */
+int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64_t ld_dout,
+                            const void* C, int64_t ldC, int64_t T, int d_c, int d_h,
+                            int G, const int* H, const int* basis_offset,
+                            void* grad_c, int64_t ld_gc, void* grad_C, int64_t ld_gC,
+                            bda_dtype dtype, bda_dtype grad_dtype, void* stream);
+
+/*
  * Tuning / testing hook: which MFMA tile the fp16/bf16 kernels use.  0 = automatic (default: the
  * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256,
  * 3 = 256 x 256 with the general streaming kernel even where its lean variant would apply.
+ * bda_kv_project_backward honours 1 (128 x 128 output tiles) and treats the rest as automatic.
  * Process-wide; returns the previous policy, or BDA_EINVAL.  Results do not depend on it beyond
  * float32 summation order inside a tile (none: the order over k is the same for every tile shape).
  */

@@ -19,7 +19,7 @@ BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
 EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_kv_project", "bda_dense_project",
-           "bda_lowrank_linear", "bda_set_tile_policy", "bda_last_error", "bda_version")
+           "bda_lowrank_linear", "bda_kv_project_backward", "bda_set_tile_policy", "bda_last_error", "bda_version")
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -64,6 +64,9 @@ def load():
     lib.bda_lowrank_linear.restype = c_int
     lib.bda_lowrank_linear.argtypes = [vp, i64, i64, c_int, c_int, c_int, c_int, vp, vp, vp, i64,
                                        c_int, vp]
+    lib.bda_kv_project_backward.restype = c_int
+    lib.bda_kv_project_backward.argtypes = [vp, i64, vp, i64, vp, i64, i64, c_int, c_int, c_int, ip, ip,
+                                            vp, i64, vp, i64, c_int, c_int, vp]
     lib.bda_set_tile_policy.restype = c_int
     lib.bda_set_tile_policy.argtypes = [c_int]
     lib.bda_last_error.restype = ctypes.c_char_p
@@ -192,3 +195,17 @@ def bda_lowrank_linear(x, ldx: int, T: int, d_in: int, r: int, d_out: int, basis
     lib = load()
     _check(lib.bda_lowrank_linear(_ptr(x), ldx, T, d_in, r, d_out, basis_offset, _ptr(Uprime),
                                   _ptr(C), _ptr(out), ld_out, dtype, stream or None))
+
+
+def bda_kv_project_backward(c, ldc: int, d_out, ld_dout: int, C, ldC: int, T: int, d_c: int, d_h: int,
+                            H: Sequence[int], basis_offset: Sequence[int], grad_c, ld_gc: int,
+                            grad_C, ld_gC: int, dtype: int, grad_dtype: Optional[int] = None,
+                            stream: int = 0) -> None:
+    lib = load()
+    G = len(H)
+    if len(basis_offset) != G:
+        raise ValueError("H and basis_offset must have one entry per group")
+    _check(lib.bda_kv_project_backward(_ptr(c), ldc, _ptr(d_out), ld_dout, _ptr(C), ldC, T, d_c, d_h, G,
+                                       _int_array(H), _int_array(basis_offset), _ptr(grad_c), ld_gc,
+                                       _ptr(grad_C), ld_gC, dtype,
+                                       dtype if grad_dtype is None else grad_dtype, stream or None))

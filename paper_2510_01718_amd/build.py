@@ -14,7 +14,7 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     # packed fp32 VALU ops stay off for every device function of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument", "-Wno-unknown-attributes",
+    "-Wno-unused-command-line-argument", "-Wno-unknown-attributes", "-Wno-inline-asm",
 ]
 
 

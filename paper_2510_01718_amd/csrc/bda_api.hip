@@ -16,22 +16,6 @@ namespace {
 
 std::atomic<int> g_tile_policy{0};
 
-struct Span {
-    const char* lo;
-    const char* hi;
-};
-
-Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld, size_t esz)
-{
-    const char* b = (const char*)p;
-    if (rows <= 0 || cols <= 0) return {b, b};
-    return {b, b + ((rows - 1) * ld + cols) * (int64_t)esz};
-}
-
-bool overlaps(Span a, Span b) { return a.lo < b.hi && b.lo < a.hi; }
-
-bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
-
 template <typename K>
 int set_max_lds(K kernel, int bytes, std::once_flag& flag)
 {
@@ -226,6 +210,9 @@ int check_dtypes(const char* fn, int dtype, int out_dtype)
 }
 
 }  // namespace
+
+int tile_policy() { return g_tile_policy.load(); }
+
 }  // namespace bda
 
 using namespace bda;

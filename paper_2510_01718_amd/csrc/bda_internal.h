@@ -28,4 +28,24 @@ inline size_t dtype_size(int dt)
     }
 }
 
+// The process-wide tile policy set by bda_set_tile_policy (0 = automatic).
+int tile_policy();
+
+// Byte range [lo, hi) of a rows x cols matrix with leading dimension ld (elements of esz bytes).
+struct Span {
+    const char* lo;
+    const char* hi;
+};
+
+inline Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld, size_t esz)
+{
+    const char* b = (const char*)p;
+    if (!p || rows <= 0 || cols <= 0) return {b, b};
+    return {b, b + ((rows - 1) * ld + cols) * (int64_t)esz};
+}
+
+inline bool overlaps(Span a, Span b) { return a.lo < b.hi && b.lo < a.hi; }
+
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
 }  // namespace bda

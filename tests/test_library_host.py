@@ -170,6 +170,20 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert lib.bda_prepare_device(fake, 512, 3, 1024, 2, 256, 0, fake, 512, 1, None, None) == -1
     assert lib.bda_prepare_device(fake, 32, 7, 64, 2, 16, 0, fake, 32, 1, None, None) == -3
     assert lib.bda_prepare_device(fake, 16, 3, 64, 2, 16, 0, fake, 32, 1, None, None) == -1
+    # gradients: bad window, ld too small, a gradient on top of an input, grad dtype, nothing asked for
+    far = ctypes.c_void_p(0x900000)
+    farther = ctypes.c_void_p(0xA00000)
+    bwd = lib.bda_kv_project_backward
+    assert bwd(fake, 64, fake, 32, fake, 32, 4, 64, 16, 1, H, bad_off, far, 64, farther, 32, 1, 1, None) == -1
+    assert b"basis_offset" in lib.bda_last_error()
+    assert bwd(fake, 64, far, 16, fake, 32, 4, 64, 16, 1, H, off, far, 64, farther, 32, 1, 1, None) == -1
+    assert bwd(fake, 64, far, 32, fake, 32, 4, 64, 16, 1, H, off, farther, 32, None, 32, 1, 1, None) == -1
+    assert bwd(fake, 64, fake, 32, fake, 32, 4, 64, 16, 1, H, off, fake, 64, farther, 32, 1, 1, None) == -1
+    assert b"overlaps" in lib.bda_last_error()
+    assert bwd(fake, 64, far, 32, fake, 32, 4, 64, 16, 1, H, off, None, 64, farther, 32, 1, 2, None) == -3
+    assert bwd(None, 64, far, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, farther, 32, 1, 1, None) == -1
+    assert b"needs c" in lib.bda_last_error()
+    assert bwd(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None) == 0
     assert lib.bda_dense_project(fake, 64, 4, 64, fake, 8, 32, fake, 32, 1, 1, None) == -1
     assert lib.bda_lowrank_linear(fake, 64, 4, 64, 8, 40, 3, fake, fake, fake, 40, 1, None) == -1
     assert lib.bda_set_tile_policy(7) == -1
