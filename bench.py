@@ -218,6 +218,22 @@ def main() -> int:
             win[name] = {"us": t_o * 1e6, "vs_first": t_o / kernel_s}
         extra["window_position_cost"] = win
         log("window position: " + ", ".join(f"{k} {v['us']:.2f} us ({v['vs_first']:.3f}x)" for k, v in win.items()))
+        # gradients of the same projection (Section "BDA Training Evaluation"): upstream gradient of
+        # the output's shape, both gradients; rotation over the same buffers (o_bufs hold whatever
+        # the forward wrote: timing only)
+        gc_b = torch.empty((T, d_c), dtype=tdt[w.dtype], device="cuda")
+        gC_b = torch.empty((K, N), dtype=tdt[w.dtype], device="cuda")
+        t_gc = bench_small(lambda i, s: bda.bda_kv_project_backward(None, d_c, o_bufs[i % R], N, C_d, N, T, d_c, d_h, H, offs,
+                                                                    gc_b, d_c, None, N, w.dtype, w.dtype, s), args.steps, args.warmup)
+        t_gC = bench_small(lambda i, s: bda.bda_kv_project_backward(c_bufs[i % R], d_c, o_bufs[i % R], N, None, N, T, d_c, d_h, H, offs,
+                                                                    None, d_c, gC_b, N, w.dtype, w.dtype, s), args.steps, args.warmup)
+        extra["backward_v2lite_T4096"] = {
+            "grad_c_us": t_gc * 1e6, "grad_c_tflops": flops / t_gc / 1e12,
+            "grad_C_us": t_gC * 1e6, "grad_C_tflops": flops / t_gC / 1e12,
+            "vs_forward": (t_gc + t_gC) / kernel_s}
+        log(f"backward: grad_c {t_gc * 1e6:.1f} us ({flops / t_gc / 1e12:.0f} TFLOP/s), grad_C {t_gC * 1e6:.1f} us "
+            f"({flops / t_gC / 1e12:.0f} TFLOP/s)")
+        del gc_b, gC_b
         # decode shapes (config 3): rotate over distinct copies of the weights so that each launch
         # streams its 3 MiB of C from HBM, not from cache
         n_w = 96

@@ -29,17 +29,17 @@ template <typename X, typename OutT, int TT, int TN, bool WEIGHT>
 int launch_mfma(const BwdArgs& a, hipStream_t st)
 {
     static std::once_flag once;
-    constexpr int lds = 2 * (64 * TT + 64 * TN) * kRowBytes;
+    constexpr int lds = BwdLds<TT, TN>::BYTES;
     const int total = a.m_tiles * a.n_tiles;
     const int grid = kNumXcd * ((total + kNumXcd - 1) / kNumXcd);
     if constexpr (WEIGHT) {
         auto kern = bwd_weight_kernel<X, OutT, TT, TN>;
         if (int rc = allow_lds(kern, lds, once)) return rc;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, a);
     } else {
         auto kern = bwd_latent_kernel<X, OutT, TT, TN>;
         if (int rc = allow_lds(kern, lds, once)) return rc;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, st, a);
     }
     return launched();
 }

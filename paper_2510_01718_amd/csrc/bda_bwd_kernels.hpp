@@ -16,11 +16,20 @@
 // The weight gradient contracts over the tokens t, along which neither c nor G is contiguous, so
 // both tiles are transposed in registers (8 x 8 blocks of 16-bit values) on their way to LDS.
 //
-// Same skeleton as gemm_mfma_kernel: 256 threads = 2 x 2 waves, each wave owns TT x TN MFMA tiles
-// of 32 x 32 (v_mfma_f32_32x32x16), contraction in chunks of 64 through a double-buffered LDS tile,
-// the next chunk's global loads in flight during the MFMAs; the operand whose index is contiguous
-// in the OUTPUT is the MFMA's row operand, so that each lane stores four consecutive elements.
+// Both contract over thousands of elements into few output tiles (T x d_c and (d_c - d_h) x N are
+// small next to T x N), so a launch has about one workgroup per compute unit and each workgroup a
+// long, latency-bound loop.  Two measures keep enough loads in flight:
+//   * a workgroup is 8 waves = 2 halves of 2 x 2 waves; the halves take alternate contraction chunks
+//     of 64 of the SAME output tile through LDS tiles of their own, and their float32 accumulators
+//     are added through LDS at the end (a fixed order: results do not depend on timing);
+//   * every half keeps two chunks in flight: chunk k + 2 is being fetched into registers while
+//     chunk k is multiplied from LDS and chunk k + 1 waits in the other register set.
+// Each wave owns TT x TN MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16); the operand whose index is
+// contiguous in the OUTPUT is the MFMA's row operand, so that each lane stores four consecutive
+// elements.
 #pragma once
+#include <type_traits>
+
 #include "bda_gemm_kernels.hpp"
 
 namespace bda {
@@ -99,16 +108,73 @@ __device__ __forceinline__ void bwd_epilogue(const f32x16 (&acc)[TN][TT], __amdg
     }
 }
 
+// LDS of one workgroup: [half 0: tok 0 | tok 1 | wgt 0 | wgt 1][half 1: the same]; after the main
+// loop the same memory carries half 1's accumulators to half 0.
+template <int TT, int TN>
+struct BwdLds {
+    static constexpr int BT = 64 * TT, BN = 64 * TN;
+    static constexpr int TOK_STAGE = BT * kRowBytes, WGT_STAGE = BN * kRowBytes;
+    static constexpr int WGT_BASE = 2 * TOK_STAGE;
+    static constexpr int HALF = 2 * (TOK_STAGE + WGT_STAGE);
+    static constexpr int BYTES = 2 * HALF;
+    static_assert(4 * TT * TN * 16 * 64 * 4 <= BYTES, "accumulator exchange must fit the staging memory");
+};
+
+// One staged chunk: 4 k-steps of TT x TN MFMAs; `extra(ks, ft)` may add MFMAs that reuse the column
+// operand's fragments.
+template <typename X, int TT, int TN, typename Extra>
+__device__ __forceinline__ void bwd_mma_chunk(const unsigned char* tok_s, const unsigned char* wgt_s,
+                                              f32x16 (&acc)[TN][TT], Extra&& extra)
+{
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        u32x4 fw[TN], ft[TT];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) fw[ni] = *(const u32x4*)(wgt_s + ni * 32 * kRowBytes + ks * 32);
+#pragma unroll
+        for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(tok_s + ti * 32 * kRowBytes + ks * 32);
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(fw[ni], ft[ti], acc[ni][ti]);
+        extra(ks, ft);
+    }
+}
+
+// Adds half 1's accumulators to half 0's through LDS (all 8 waves call this after the last chunk).
+template <int TT, int TN>
+__device__ __forceinline__ void bwd_reduce_halves(unsigned char* smem, f32x16 (&acc)[TN][TT], int half, int w4, int lane)
+{
+    __syncthreads();   // every wave is done reading the staged tiles
+    float* x = (float*)smem + (w4 * (TT * TN * 16)) * 64 + lane;
+    if (half == 1) {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int ti = 0; ti < TT; ++ti)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) x[((ni * TT + ti) * 16 + r) * 64] = acc[ni][ti][r];
+    }
+    __syncthreads();
+    if (half == 0) {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int ti = 0; ti < TT; ++ti)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ni][ti][r] += x[((ni * TT + ti) * 16 + r) * 64];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Latent gradient.  Output tile: (64 TT) tokens x (64 TN) latent columns.  Column operand ("tok")
 // = G rows, row operand ("wgt") = rows of Wfull, one per latent column of the tile.
 // ---------------------------------------------------------------------------------------------
 template <typename X, typename OutT, int TT, int TN>
-__global__ __launch_bounds__(256) void bwd_latent_kernel(const BwdArgs p)
+__global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
 {
-    constexpr int BT = 64 * TT, BN = 64 * TN;
-    constexpr int TOK_STAGE = BT * kRowBytes, WGT_STAGE = BN * kRowBytes;
-    constexpr int WGT_BASE = 2 * TOK_STAGE;
+    using L = BwdLds<TT, TN>;
+    constexpr int BT = L::BT, BN = L::BN;
     constexpr int TOK_LOADS = BT / 32, WGT_LOADS = BN / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -116,12 +182,14 @@ __global__ __launch_bounds__(256) void bwd_latent_kernel(const BwdArgs p)
     if (tile < 0) return;
     const int mt = tile / p.n_tiles, nt = tile % p.n_tiles;   // the column tiles of one token tile share its G rows
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;                        // thread within its half
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wt = wave >> 1, wn = wave & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int half = wave >> 2, w4 = wave & 3;
+    const int wt = w4 >> 1, wn = w4 & 1;
     const int l31 = lane & 31, lhi = lane >> 5;
     const int tq = tid & 7, trow = tid >> 3;
+    unsigned char* const lds = smem + half * L::HALF;
 
     const int64_t t0 = (int64_t)mt * BT;
     const int64_t rows_left = p.T - t0;
@@ -135,41 +203,90 @@ __global__ __launch_bounds__(256) void bwd_latent_kernel(const BwdArgs p)
                                                 ((rows_left - 1) * p.ldo + cols_left) * (int64_t)sizeof(OutT));
     const uint32_t g_row_bytes = (uint32_t)(p.ldg * 2), c_row_bytes = (uint32_t)(p.ldC * 2);
 
-    u32x4 tok_reg[TOK_LOADS], wgt_reg[WGT_LOADS];
+    int n_chunks = 0;
+    for (int g = 0; g < p.n_groups; ++g) n_chunks += (int)((p.col_start[g + 1] - p.col_start[g] + 63) >> 6);
+    const int n_it = (n_chunks + 1) >> 1;                     // chunks of this half: 2 it + half
 
-    // chunk cursor: (group, first column); chunks never straddle groups
-    auto advance = [&](int& g, int64_t& nc) {
-        nc += 64;
-        if (nc >= p.col_start[g + 1]) {
-            ++g;
-            nc = p.col_start[g < p.n_groups ? g : p.n_groups];
-        }
+    // Cursor over this half's chunks (every second chunk of 64 output columns; chunks never
+    // straddle groups).  All scalar; the group tables are read again only when a group ends.
+    struct Cursor {
+        int g, q, cnt;      // group, chunk within the group, chunks of the group
+        int start, end;     // output columns of the group
+        int off;            // basis window start of the group
+        int jc;             // (64 q) % d_h: window column of the chunk's first output column
+        bool valid;
     };
-    auto load_chunk = [&](int g, int64_t nc) {
-        const int64_t col = nc + tq * 8;
-        const bool col_ok = col < p.col_start[g + 1];
-        const uint32_t col_bytes = (uint32_t)col * 2u;
+    auto enter_group = [&](Cursor& k) {
+        k.start = (int)p.col_start[k.g];
+        k.end = (int)p.col_start[k.g + 1];
+        k.cnt = (k.end - k.start + 63) >> 6;
+        k.off = p.a_off[k.g];
+    };
+    auto settle = [&](Cursor& k) {        // moves on while q lies beyond the group's chunks
+        bool crossed = false;
+        while (k.valid && k.q >= k.cnt) {
+            k.q -= k.cnt;
+            if (++k.g >= p.n_groups) k.valid = false;
+            else enter_group(k);
+            crossed = true;
+        }
+        if (crossed) k.jc = 64 * k.q;
+        while (k.jc >= p.d_h) k.jc -= p.d_h;
+    };
+    auto advance = [&](Cursor& k) {
+        if (!k.valid) return;
+        k.q += 2;
+        k.jc += 128;
+        settle(k);
+    };
+    Cursor cur;                           // chunk being multiplied; nxt, ld: one and two iterations ahead
+    cur.g = 0;
+    cur.q = half;
+    cur.jc = 64 * half;
+    cur.valid = true;
+    enter_group(cur);
+    settle(cur);
+    Cursor nxt = cur;
+    advance(nxt);
+    Cursor ld = nxt;
+    advance(ld);
+
+    // per-lane pieces of the load offsets that do not depend on the chunk
+    uint32_t tok_base[TOK_LOADS];
+#pragma unroll
+    for (int i = 0; i < TOK_LOADS; ++i) tok_base[i] = (uint32_t)(trow + 32 * i) * g_row_bytes + (uint32_t)(tq * 16);
+
+    u32x4 tok_reg[2][TOK_LOADS], wgt_reg[2][WGT_LOADS];
+    auto load_chunk = [&](auto set, const Cursor& k) {
+        constexpr int S = decltype(set)::value;
+        const int nc = k.start + 64 * k.q;
+        const int rem = k.valid ? k.end - nc : 0;             // columns of the group from nc on
+        const bool col_ok = tq * 8 < rem;
+        const uint32_t chunk_bytes = (uint32_t)nc * 2u;
 #pragma unroll
         for (int i = 0; i < TOK_LOADS; ++i) {
-            const uint32_t voff = col_ok ? (uint32_t)(trow + 32 * i) * g_row_bytes + col_bytes : kBadOffset;
-            tok_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(rG, voff, 0, 0);
+            uint32_t voff = col_ok ? tok_base[i] + chunk_bytes : kBadOffset;
+            asm volatile("" : "+v"(voff));                    // one load, not one per branch
+            tok_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rG, voff, 0, 0);
         }
-        const int off = p.a_off[g];
 #pragma unroll
         for (int i = 0; i < WGT_LOADS; ++i) {
             const int l = l0 + trow + 32 * i;                                 // latent column of this LDS row
-            const int row = l < off ? l : l - p.d_h;                          // its row of C
-            const bool ok = col_ok && l < p.d_c && (l < off || l >= off + p.d_h);
-            wgt_reg[i] = __builtin_amdgcn_raw_buffer_load_b128(rC, ok ? (uint32_t)row * c_row_bytes + col_bytes : kBadOffset, 0, 0);
+            const int row = l < k.off ? l : l - p.d_h;                        // its row of C
+            const bool ok = col_ok && l < p.d_c && (l < k.off || l >= k.off + p.d_h);
+            uint32_t voff = ok ? (uint32_t)row * c_row_bytes + (uint32_t)(tq * 16) + chunk_bytes : kBadOffset;
+            asm volatile("" : "+v"(voff));
+            wgt_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rC, voff, 0, 0);
         }
     };
-    auto store_chunk = [&](int stage) {
-        unsigned char* tok_s = smem + stage * TOK_STAGE;
-        unsigned char* wgt_s = smem + WGT_BASE + stage * WGT_STAGE;
+    auto store_chunk = [&](auto set) {
+        constexpr int S = decltype(set)::value;
+        unsigned char* tok_s = lds + S * L::TOK_STAGE;
+        unsigned char* wgt_s = lds + L::WGT_BASE + S * L::WGT_STAGE;
 #pragma unroll
-        for (int i = 0; i < TOK_LOADS; ++i) *(u32x4*)(tok_s + lds_off(trow + 32 * i, tq)) = tok_reg[i];
+        for (int i = 0; i < TOK_LOADS; ++i) *(u32x4*)(tok_s + lds_off(trow + 32 * i, tq)) = tok_reg[S][i];
 #pragma unroll
-        for (int i = 0; i < WGT_LOADS; ++i) *(u32x4*)(wgt_s + lds_off(trow + 32 * i, tq)) = wgt_reg[i];
+        for (int i = 0; i < WGT_LOADS; ++i) *(u32x4*)(wgt_s + lds_off(trow + 32 * i, tq)) = wgt_reg[S][i];
     };
 
     f32x16 acc[TN][TT];
@@ -180,86 +297,79 @@ __global__ __launch_bounds__(256) void bwd_latent_kernel(const BwdArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[ni][ti][r] = 0.0f;
 
-    int n_chunks = 0;
-    for (int g = 0; g < p.n_groups; ++g) n_chunks += (int)((p.col_start[g + 1] - p.col_start[g] + 63) >> 6);
-
     const int tok_rd = (wt * (32 * TT) + l31) * kRowBytes + lhi * 16;
-    const int wgt_rd = WGT_BASE + (wn * (32 * TN) + l31) * kRowBytes + lhi * 16;
+    const int wgt_rd = L::WGT_BASE + (wn * (32 * TN) + l31) * kRowBytes + lhi * 16;
     const int colm0 = l0 + wn * (32 * TN);           // first latent column of this wave's MFMA tiles
 
-    int g_cur = 0, g_nxt = 0;
-    int64_t nc_cur = 0, nc_nxt = 0;
-    load_chunk(0, 0);
-    store_chunk(0);
-    advance(g_nxt, nc_nxt);
-    __syncthreads();
-    for (int kc = 0; kc < n_chunks; ++kc) {
-        const bool more = kc + 1 < n_chunks;
-        if (more) load_chunk(g_nxt, nc_nxt);
-        const unsigned char* tok_s = smem + tok_rd + (kc & 1) * TOK_STAGE;
-        const unsigned char* wgt_s = smem + wgt_rd + (kc & 1) * WGT_STAGE;
-        const int off = p.a_off[g_cur];
-        const int jc = (int)((nc_cur - p.col_start[g_cur]) % p.d_h);   // window column of the chunk's first output column
+    // an iteration multiplies this half's chunk `cur` from LDS stage S, fetches chunk `ld` into
+    // register set S and moves chunk `nxt` from register set 1 - S to LDS
+    auto iteration = [&](auto set) {
+        constexpr int S = decltype(set)::value;
+        load_chunk(set, ld);
+        if (cur.valid) {
+            const int off = cur.off, jc = cur.jc;
+            bwd_mma_chunk<X, TT, TN>(lds + tok_rd + S * L::TOK_STAGE, lds + wgt_rd + S * L::WGT_STAGE, acc,
+                                     [&](int ks, const u32x4 (&ft)[TT]) {
+                // window rows of Wfull: output columns nc + 16 ks + k' feed latent column off + jk + k'
+                int jk = jc + 16 * ks;
+                if (jk >= p.d_h) jk -= p.d_h;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 fw[TN], ft[TT];
+                for (int ni = 0; ni < TN; ++ni) {
+                    const int d = off + jk - (colm0 + 32 * ni);
+                    if (d > -16 && d < 32) {   // uniform over the wave
+                        const u32x4 f = shifted_identity_frag<X>(d, l31, lhi);
 #pragma unroll
-            for (int ni = 0; ni < TN; ++ni) fw[ni] = *(const u32x4*)(wgt_s + ni * 32 * kRowBytes + ks * 32);
-#pragma unroll
-            for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(tok_s + ti * 32 * kRowBytes + ks * 32);
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(fw[ni], ft[ti], acc[ni][ti]);
-            // window rows of Wfull: output columns nc + 16 ks + k' feed latent column off + jk + k'
-            int jk = jc + 16 * ks;
-            if (jk >= p.d_h) jk -= p.d_h;
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                const int d = off + jk - (colm0 + 32 * ni);
-                if (d > -16 && d < 32) {   // uniform over the wave
-                    const u32x4 f = shifted_identity_frag<X>(d, l31, lhi);
-#pragma unroll
-                    for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(f, ft[ti], acc[ni][ti]);
+                        for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(f, ft[ti], acc[ni][ti]);
+                    }
                 }
-            }
+            });
         }
-        if (more) store_chunk((kc + 1) & 1);
-        g_cur = g_nxt;
-        nc_cur = nc_nxt;
-        if (more) advance(g_nxt, nc_nxt);
+        store_chunk(std::integral_constant<int, 1 - S>{});
+        cur = nxt;
+        nxt = ld;
+        advance(ld);
+        __syncthreads();
+    };
+
+    {
+        // prologue: chunks `cur` and `nxt` into the two register sets, `cur` on to LDS
+        load_chunk(std::integral_constant<int, 0>{}, cur);
+        load_chunk(std::integral_constant<int, 1>{}, nxt);
+        store_chunk(std::integral_constant<int, 0>{});
         __syncthreads();
     }
-    bwd_epilogue<X, OutT, TT, TN>(acc, rD, p.ldo, cols_left, wt, wn, l31, lhi);
+    for (int it = 0; it < n_it; it += 2) {
+        iteration(std::integral_constant<int, 0>{});
+        iteration(std::integral_constant<int, 1>{});
+    }
+    bwd_reduce_halves<TT, TN>(smem, acc, half, w4, lane);
+    if (half == 0) bwd_epilogue<X, OutT, TT, TN>(acc, rD, p.ldo, cols_left, wt, wn, l31, lhi);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Weight gradient.  Output tile: (64 TT) rows of C x (64 TN) columns.  Column operand ("tok") =
 // latent columns Bbar(i) of c, row operand ("wgt") = columns of G; both are read as 8 (tokens) x 8
-// blocks and transposed in registers.
+// blocks and transposed in registers.  The BT + BN <= 256 blocks of a chunk go one to a thread.
 // ---------------------------------------------------------------------------------------------
 template <typename X, typename OutT, int TT, int TN>
-__global__ __launch_bounds__(256) void bwd_weight_kernel(const BwdArgs p)
+__global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
 {
-    constexpr int BT = 64 * TT, BN = 64 * TN;
-    constexpr int TOK_STAGE = BT * kRowBytes, WGT_STAGE = BN * kRowBytes;
-    constexpr int WGT_BASE = 2 * TOK_STAGE;
-    constexpr int TOK_BLOCKS = (BT + 255) / 256, WGT_BLOCKS = (BN + 255) / 256;
+    using L = BwdLds<TT, TN>;
+    constexpr int BT = L::BT, BN = L::BN;
+    static_assert(BT + BN <= 256, "one 8 x 8 block per thread");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tile = bwd_tile_of_block(p.m_tiles * p.n_tiles);
     if (tile < 0) return;
     const int nt = tile / p.m_tiles, mt = tile % p.m_tiles;   // the row tiles of one column tile share its G columns
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wt = wave >> 1, wn = wave & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int half = wave >> 2, w4 = wave & 3;
+    const int wt = w4 >> 1, wn = w4 & 1;
     const int l31 = lane & 31, lhi = lane >> 5;
-    // small tiles: the two operands are fetched by different halves of the workgroup
-    const int tid_w = (BT <= 128 && BN <= 128) ? (tid ^ 128) : tid;
-    const int kq_t = tid & 7, blk_t = tid >> 3;       // "tok": 8-token block within the chunk, 8-row block of the tile
-    const int kq_w = tid_w & 7, blk_w = tid_w >> 3;
+    unsigned char* const lds = smem + half * L::HALF;
 
     int g = 0;
     while (g + 1 < p.n_groups && nt >= p.tile_start[g + 1]) ++g;
@@ -271,63 +381,50 @@ __global__ __launch_bounds__(256) void bwd_weight_kernel(const BwdArgs p)
 
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.out + ((int64_t)i0 * p.ldo + n0) * (int64_t)sizeof(OutT),
                                                 ((int64_t)(rows_left - 1) * p.ldo + cols_left) * (int64_t)sizeof(OutT));
-    const uint32_t c_row_bytes = (uint32_t)(p.ldc * 2), g_row_bytes = (uint32_t)(p.ldg * 2);
 
-    // block offsets inside a chunk of 64 tokens (the chunk's first token is the descriptor's base)
-    uint32_t tok_voff[TOK_BLOCKS], wgt_voff[WGT_BLOCKS];
-#pragma unroll
-    for (int b = 0; b < TOK_BLOCKS; ++b) {
-        const int i = (blk_t + 32 * b) * 8;                       // row of C, relative to the tile
-        const int ia = i0 + i;
-        const int col = ia < a_off ? ia : ia + p.d_h;             // its latent column
-        tok_voff[b] = (i < BT && i < rows_left) ? (uint32_t)(kq_t * 8) * c_row_bytes + (uint32_t)col * 2u : kBadOffset;
+    // this thread's block: 8 tokens (kq) x 8 rows of C (is_tok) or 8 columns of G
+    const bool is_tok = __builtin_amdgcn_readfirstlane(tid < BT);   // uniform per wave: BT is a multiple of 64
+    const bool has_block = tid < BT + BN;
+    const int blk = is_tok ? tid : tid - BT;
+    const int kq = blk & 7, r8 = (blk >> 3) * 8;                    // r8: first tile row (tok) / tile column (wgt)
+    const uint32_t row_bytes = (uint32_t)((is_tok ? p.ldc : p.ldg) * 2);
+    uint32_t voff0;
+    if (is_tok) {
+        const int ia = i0 + r8;
+        const int col = ia < a_off ? ia : ia + p.d_h;               // latent column of row ia of C
+        voff0 = r8 < rows_left ? (uint32_t)(kq * 8) * row_bytes + (uint32_t)col * 2u : kBadOffset;
+    } else {
+        voff0 = (has_block && r8 < cols_left) ? (uint32_t)(kq * 8) * row_bytes + (uint32_t)r8 * 2u : kBadOffset;
     }
-#pragma unroll
-    for (int b = 0; b < WGT_BLOCKS; ++b) {
-        const int n = (blk_w + 32 * b) * 8;
-        wgt_voff[b] = (n < BN && n < cols_left) ? (uint32_t)(kq_w * 8) * g_row_bytes + (uint32_t)n * 2u : kBadOffset;
-    }
+    const int n_chunks = (int)((p.T + 63) >> 6);
+    const int n_it = (n_chunks + 1) >> 1;
 
-    u32x4 tok_reg[TOK_BLOCKS][8], wgt_reg[WGT_BLOCKS][8];
-    auto load_chunk = [&](int kc) {
-        // descriptors end with the last token, so token rows past T read as zero
-        const int64_t t = (int64_t)kc * 64;
+    u32x4 reg[2][8];
+    auto load_chunk = [&](auto set, int it) {
+        constexpr int S = decltype(set)::value;
+        // descriptors end with the last token, so token rows past T (and whole chunks past the
+        // last one) read as zero
+        const int64_t t = (int64_t)(2 * it + half) * 64;
         const int64_t rows = p.T - t > 64 ? 64 : p.T - t;
-        const __amdgpu_buffer_rsrc_t rA = make_rsrc((const char*)p.c + t * p.ldc * 2, ((rows - 1) * p.ldc + p.d_c) * 2);
-        const __amdgpu_buffer_rsrc_t rB = make_rsrc((const char*)p.g + (t * p.ldg + n0) * 2, ((rows - 1) * p.ldg + cols_left) * 2);
+        const int64_t tb = rows > 0 ? t : 0;
+        const __amdgpu_buffer_rsrc_t r = is_tok
+            ? make_rsrc((const char*)p.c + tb * p.ldc * 2, rows > 0 ? ((rows - 1) * p.ldc + p.d_c) * 2 : 0)
+            : make_rsrc((const char*)p.g + (tb * p.ldg + n0) * 2, rows > 0 ? ((rows - 1) * p.ldg + cols_left) * 2 : 0);
 #pragma unroll
-        for (int b = 0; b < TOK_BLOCKS; ++b)
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                tok_reg[b][e] = __builtin_amdgcn_raw_buffer_load_b128(rA, tok_voff[b] == kBadOffset ? kBadOffset : tok_voff[b] + (uint32_t)e * c_row_bytes, 0, 0);
-#pragma unroll
-        for (int b = 0; b < WGT_BLOCKS; ++b)
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                wgt_reg[b][e] = __builtin_amdgcn_raw_buffer_load_b128(rB, wgt_voff[b] == kBadOffset ? kBadOffset : wgt_voff[b] + (uint32_t)e * g_row_bytes, 0, 0);
-    };
-    auto store_chunk = [&](int stage) {
-        unsigned char* tok_s = smem + stage * TOK_STAGE;
-        unsigned char* wgt_s = smem + WGT_BASE + stage * WGT_STAGE;
-#pragma unroll
-        for (int b = 0; b < TOK_BLOCKS; ++b) {
-            const int r = (blk_t + 32 * b) * 8;
-            if (r < BT) {
-                u32x4 tr[8];
-                transpose8x8_b16(tok_reg[b], tr);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) *(u32x4*)(tok_s + lds_off(r + j, kq_t)) = tr[j];
-            }
+        for (int e = 0; e < 8; ++e) {
+            uint32_t voff = voff0 == kBadOffset ? kBadOffset : voff0 + (uint32_t)e * row_bytes;
+            asm volatile("" : "+v"(voff));                    // one load, not one per branch
+            reg[S][e] = __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0);
         }
+    };
+    auto store_chunk = [&](auto set) {
+        constexpr int S = decltype(set)::value;
+        if (has_block) {
+            unsigned char* dst = lds + (is_tok ? S * L::TOK_STAGE : L::WGT_BASE + S * L::WGT_STAGE);
+            u32x4 tr[8];
+            transpose8x8_b16(reg[S], tr);
 #pragma unroll
-        for (int b = 0; b < WGT_BLOCKS; ++b) {
-            const int r = (blk_w + 32 * b) * 8;
-            if (r < BN) {
-                u32x4 tr[8];
-                transpose8x8_b16(wgt_reg[b], tr);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) *(u32x4*)(wgt_s + lds_off(r + j, kq_w)) = tr[j];
-            }
+            for (int j = 0; j < 8; ++j) *(u32x4*)(dst + lds_off(r8 + j, kq)) = tr[j];
         }
     };
 
@@ -339,33 +436,29 @@ __global__ __launch_bounds__(256) void bwd_weight_kernel(const BwdArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[ni][ti][r] = 0.0f;
 
-    const int n_chunks = (int)((p.T + 63) >> 6);
     const int tok_rd = (wt * (32 * TT) + l31) * kRowBytes + lhi * 16;
-    const int wgt_rd = WGT_BASE + (wn * (32 * TN) + l31) * kRowBytes + lhi * 16;
-    load_chunk(0);
-    store_chunk(0);
-    __syncthreads();
-    for (int kc = 0; kc < n_chunks; ++kc) {
-        const bool more = kc + 1 < n_chunks;
-        if (more) load_chunk(kc + 1);
-        const unsigned char* tok_s = smem + tok_rd + (kc & 1) * TOK_STAGE;
-        const unsigned char* wgt_s = smem + wgt_rd + (kc & 1) * WGT_STAGE;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 fw[TN], ft[TT];
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) fw[ni] = *(const u32x4*)(wgt_s + ni * 32 * kRowBytes + ks * 32);
-#pragma unroll
-            for (int ti = 0; ti < TT; ++ti) ft[ti] = *(const u32x4*)(tok_s + ti * 32 * kRowBytes + ks * 32);
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(fw[ni], ft[ti], acc[ni][ti]);
-        }
-        if (more) store_chunk((kc + 1) & 1);
+    const int wgt_rd = L::WGT_BASE + (wn * (32 * TN) + l31) * kRowBytes + lhi * 16;
+
+    auto iteration = [&](auto set, int it) {
+        constexpr int S = decltype(set)::value;
+        load_chunk(set, it + 2);
+        if (2 * it + half < n_chunks)
+            bwd_mma_chunk<X, TT, TN>(lds + tok_rd + S * L::TOK_STAGE, lds + wgt_rd + S * L::WGT_STAGE, acc,
+                                     [](int, const u32x4 (&)[TT]) {});
+        store_chunk(std::integral_constant<int, 1 - S>{});
         __syncthreads();
+    };
+
+    load_chunk(std::integral_constant<int, 0>{}, 0);
+    load_chunk(std::integral_constant<int, 1>{}, 1);
+    store_chunk(std::integral_constant<int, 0>{});
+    __syncthreads();
+    for (int it = 0; it < n_it; it += 2) {
+        iteration(std::integral_constant<int, 0>{}, it);
+        iteration(std::integral_constant<int, 1>{}, it + 1);
     }
-    bwd_epilogue<X, OutT, TT, TN>(acc, rD, p.ldo, cols_left, wt, wn, l31, lhi);
+    bwd_reduce_halves<TT, TN>(smem, acc, half, w4, lane);
+    if (half == 0) bwd_epilogue<X, OutT, TT, TN>(acc, rD, p.ldo, cols_left, wt, wn, l31, lhi);
 }
 
 // ---------------------------------------------------------------------------------------------
