@@ -29,7 +29,7 @@ template <typename X, typename OutT, int TT, int TN, bool WEIGHT>
 int launch_mfma(const BwdArgs& a, hipStream_t st)
 {
     static std::once_flag once;
-    constexpr int lds = BwdLds<TT, TN>::BYTES;
+    constexpr int lds = WEIGHT ? BwdWeightLds<TT, TN>::BYTES : BwdLds<TT, TN>::BYTES;
     const int total = a.m_tiles * a.n_tiles;
     const int grid = kNumXcd * ((total + kNumXcd - 1) / kNumXcd);
     if constexpr (WEIGHT) {

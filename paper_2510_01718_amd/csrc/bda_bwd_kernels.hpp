@@ -14,7 +14,7 @@
 // loaded: where a 32-column MFMA tile of gc meets the window, the staged G fragment is multiplied
 // by a constant 0/1 fragment, which sums the heads' gradients in float32 inside the accumulator.
 // The weight gradient contracts over the tokens t, along which neither c nor G is contiguous, so
-// both tiles are transposed in registers (8 x 8 blocks of 16-bit values) on their way to LDS.
+// both tiles keep their memory layout in LDS and the fragments come from transposing LDS reads.
 //
 // Both contract over thousands of elements into few output tiles (T x d_c and (d_c - d_h) x N are
 // small next to T x N), so a launch has about one workgroup per compute unit and each workgroup a
@@ -348,15 +348,35 @@ __global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
 
 // ---------------------------------------------------------------------------------------------
 // Weight gradient.  Output tile: (64 TT) rows of C x (64 TN) columns.  Column operand ("tok") =
-// latent columns Bbar(i) of c, row operand ("wgt") = columns of G; both are read as 8 (tokens) x 8
-// blocks and transposed in registers.  The BT + BN <= 256 blocks of a chunk go one to a thread.
+// latent columns Bbar(i) of c, row operand ("wgt") = columns of G.  The contraction index (token)
+// is the slow index of both in memory, so both tiles are copied to LDS as they are -- one LDS row
+// per token, coalesced on both sides -- and the fragments are read with the transposing LDS read
+// (ds_read_b64_tr_b16): each lane names four consecutive columns of one token row and receives
+// four consecutive tokens of one column.  Rows are padded by 32 bytes, so that the four token rows
+// one such read touches lie on different banks.
 // ---------------------------------------------------------------------------------------------
+template <int TT, int TN>
+struct BwdWeightLds {
+    static constexpr int BT = 64 * TT, BN = 64 * TN;
+    static constexpr int TOK_PITCH = BT * 2 + 32, WGT_PITCH = BN * 2 + 32;   // bytes per token row
+    static constexpr int TOK_STAGE = 64 * TOK_PITCH, WGT_STAGE = 64 * WGT_PITCH;
+    static constexpr int WGT_BASE = 2 * TOK_STAGE;
+    static constexpr int HALF = 2 * (TOK_STAGE + WGT_STAGE);
+    static constexpr int BYTES = 2 * HALF;
+    static_assert(4 * TT * TN * 16 * 64 * 4 <= BYTES, "accumulator exchange must fit the staging memory");
+};
+
 template <typename X, typename OutT, int TT, int TN>
 __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
 {
-    using L = BwdLds<TT, TN>;
+    using L = BwdWeightLds<TT, TN>;
     constexpr int BT = L::BT, BN = L::BN;
-    static_assert(BT + BN <= 256, "one 8 x 8 block per thread");
+    constexpr int TOK_PER_ROW = BT / 8, WGT_PER_ROW = BN / 8;       // 16-byte pieces per token row
+    constexpr int TOK_LOADS = 64 * TOK_PER_ROW / 256, WGT_LOADS = 64 * WGT_PER_ROW / 256;
+    constexpr int TOK_ROWS_PER_PASS = 256 / TOK_PER_ROW, WGT_ROWS_PER_PASS = 256 / WGT_PER_ROW;
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+    typedef __attribute__((address_space(3))) unsigned char* lds_u8;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tile = bwd_tile_of_block(p.m_tiles * p.n_tiles);
@@ -378,54 +398,66 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
     const int i0 = mt * BT;
     const int rows_left = p.K - i0;
     const int a_off = p.a_off[g];
+    const int64_t T = p.T;
+    const char* const c_base = (const char*)p.c;
+    const char* const g_base = (const char*)p.g + n0 * 2;
+    const int64_t c_pitch = p.ldc * 2, g_pitch = p.ldg * 2;
+    const int d_c_bytes = p.d_c * 2;
 
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.out + ((int64_t)i0 * p.ldo + n0) * (int64_t)sizeof(OutT),
                                                 ((int64_t)(rows_left - 1) * p.ldo + cols_left) * (int64_t)sizeof(OutT));
 
-    // this thread's block: 8 tokens (kq) x 8 rows of C (is_tok) or 8 columns of G
-    const bool is_tok = __builtin_amdgcn_readfirstlane(tid < BT);   // uniform per wave: BT is a multiple of 64
-    const bool has_block = tid < BT + BN;
-    const int blk = is_tok ? tid : tid - BT;
-    const int kq = blk & 7, r8 = (blk >> 3) * 8;                    // r8: first tile row (tok) / tile column (wgt)
-    const uint32_t row_bytes = (uint32_t)((is_tok ? p.ldc : p.ldg) * 2);
-    uint32_t voff0;
-    if (is_tok) {
-        const int ia = i0 + r8;
-        const int col = ia < a_off ? ia : ia + p.d_h;               // latent column of row ia of C
-        voff0 = r8 < rows_left ? (uint32_t)(kq * 8) * row_bytes + (uint32_t)col * 2u : kBadOffset;
-    } else {
-        voff0 = (has_block && r8 < cols_left) ? (uint32_t)(kq * 8) * row_bytes + (uint32_t)r8 * 2u : kBadOffset;
+    // this thread's pieces: tok piece (row tid / TOK_PER_ROW + pass * TOK_ROWS_PER_PASS, 16-byte piece
+    // tid % TOK_PER_ROW), the same for wgt; offsets relative to the chunk's first token
+    uint32_t tok_voff, wgt_voff, tok_lds, wgt_lds;
+    {
+        const int piece = tid % TOK_PER_ROW, row = tid / TOK_PER_ROW;
+        const int ia = i0 + piece * 8;                              // row of C
+        const int col = ia < a_off ? ia : ia + p.d_h;               // its latent column
+        tok_voff = piece * 8 < rows_left ? (uint32_t)row * (uint32_t)c_pitch + (uint32_t)col * 2u : kBadOffset;
+        tok_lds = (uint32_t)(row * L::TOK_PITCH + piece * 16);
     }
-    const int n_chunks = (int)((p.T + 63) >> 6);
+    {
+        const int piece = tid % WGT_PER_ROW, row = tid / WGT_PER_ROW;
+        wgt_voff = piece * 8 < cols_left ? (uint32_t)row * (uint32_t)g_pitch + (uint32_t)piece * 16u : kBadOffset;
+        wgt_lds = (uint32_t)(row * L::WGT_PITCH + piece * 16);
+    }
+    const uint32_t tok_pass = (uint32_t)TOK_ROWS_PER_PASS * (uint32_t)c_pitch;
+    const uint32_t wgt_pass = (uint32_t)WGT_ROWS_PER_PASS * (uint32_t)g_pitch;
+    const int n_chunks = (int)((T + 63) >> 6);
     const int n_it = (n_chunks + 1) >> 1;
 
-    u32x4 reg[2][8];
+    u32x4 tok_reg[2][TOK_LOADS], wgt_reg[2][WGT_LOADS];
     auto load_chunk = [&](auto set, int it) {
         constexpr int S = decltype(set)::value;
         // descriptors end with the last token, so token rows past T (and whole chunks past the
         // last one) read as zero
         const int64_t t = (int64_t)(2 * it + half) * 64;
-        const int64_t rows = p.T - t > 64 ? 64 : p.T - t;
+        const int64_t rows = T - t > 64 ? 64 : T - t;
         const int64_t tb = rows > 0 ? t : 0;
-        const __amdgpu_buffer_rsrc_t r = is_tok
-            ? make_rsrc((const char*)p.c + tb * p.ldc * 2, rows > 0 ? ((rows - 1) * p.ldc + p.d_c) * 2 : 0)
-            : make_rsrc((const char*)p.g + (tb * p.ldg + n0) * 2, rows > 0 ? ((rows - 1) * p.ldg + cols_left) * 2 : 0);
+        const __amdgpu_buffer_rsrc_t rA = make_rsrc(c_base + tb * c_pitch, rows > 0 ? (rows - 1) * c_pitch + d_c_bytes : 0);
+        const __amdgpu_buffer_rsrc_t rB = make_rsrc(g_base + tb * g_pitch, rows > 0 ? (rows - 1) * g_pitch + cols_left * 2 : 0);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            uint32_t voff = voff0 == kBadOffset ? kBadOffset : voff0 + (uint32_t)e * row_bytes;
+        for (int i = 0; i < TOK_LOADS; ++i) {
+            uint32_t voff = tok_voff == kBadOffset ? kBadOffset : tok_voff + (uint32_t)i * tok_pass;
             asm volatile("" : "+v"(voff));                    // one load, not one per branch
-            reg[S][e] = __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0);
+            tok_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rA, voff, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WGT_LOADS; ++i) {
+            uint32_t voff = wgt_voff == kBadOffset ? kBadOffset : wgt_voff + (uint32_t)i * wgt_pass;
+            asm volatile("" : "+v"(voff));
+            wgt_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rB, voff, 0, 0);
         }
     };
     auto store_chunk = [&](auto set) {
         constexpr int S = decltype(set)::value;
-        if (has_block) {
-            unsigned char* dst = lds + (is_tok ? S * L::TOK_STAGE : L::WGT_BASE + S * L::WGT_STAGE);
-            u32x4 tr[8];
-            transpose8x8_b16(reg[S], tr);
+        unsigned char* tok_s = lds + S * L::TOK_STAGE + tok_lds;
+        unsigned char* wgt_s = lds + L::WGT_BASE + S * L::WGT_STAGE + wgt_lds;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) *(u32x4*)(dst + lds_off(r8 + j, kq)) = tr[j];
-        }
+        for (int i = 0; i < TOK_LOADS; ++i) *(u32x4*)(tok_s + i * TOK_ROWS_PER_PASS * L::TOK_PITCH) = tok_reg[S][i];
+#pragma unroll
+        for (int i = 0; i < WGT_LOADS; ++i) *(u32x4*)(wgt_s + i * WGT_ROWS_PER_PASS * L::WGT_PITCH) = wgt_reg[S][i];
     };
 
     f32x16 acc[TN][TT];
@@ -436,15 +468,41 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[ni][ti][r] = 0.0f;
 
-    const int tok_rd = (wt * (32 * TT) + l31) * kRowBytes + lhi * 16;
-    const int wgt_rd = L::WGT_BASE + (wn * (32 * TN) + l31) * kRowBytes + lhi * 16;
+    // transposing reads: lane (16-lane group q = lane / 16, s = lane % 16) names token row
+    // 8 (q / 2) + s / 4 (+ 16 ks, + 4 for the upper half of the fragment) and columns
+    // 16 (q % 2) + 4 (s % 4) .. + 3 of an MFMA tile's 32; it receives tokens 8 lhi .. 8 lhi + 7 of
+    // column l31 -- the MFMA operand layout
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8)lds;
+    const int c_s = lane & 15, c_q = lane >> 4;
+    const int fr_row = 8 * (c_q >> 1) + (c_s >> 2), fr_col = 16 * (c_q & 1) + 4 * (c_s & 3);
+    const uint32_t a_tok = lds0 + (uint32_t)(fr_row * L::TOK_PITCH + (wt * (32 * TT) + fr_col) * 2);
+    const uint32_t a_wgt = lds0 + (uint32_t)(L::WGT_BASE + fr_row * L::WGT_PITCH + (wn * (32 * TN) + fr_col) * 2);
+    auto frag = [&](uint32_t addr, int pitch) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(uintptr_t)addr);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(uintptr_t)(addr + 4 * pitch));
+        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+        return (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
+    };
 
     auto iteration = [&](auto set, int it) {
         constexpr int S = decltype(set)::value;
         load_chunk(set, it + 2);
-        if (2 * it + half < n_chunks)
-            bwd_mma_chunk<X, TT, TN>(lds + tok_rd + S * L::TOK_STAGE, lds + wgt_rd + S * L::WGT_STAGE, acc,
-                                     [](int, const u32x4 (&)[TT]) {});
+        if (2 * it + half < n_chunks) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                u32x4 fw[TN], ft[TT];
+#pragma unroll
+                for (int ni = 0; ni < TN; ++ni)
+                    fw[ni] = frag(a_wgt + S * L::WGT_STAGE + 16 * ks * L::WGT_PITCH + ni * 64, L::WGT_PITCH);
+#pragma unroll
+                for (int ti = 0; ti < TT; ++ti)
+                    ft[ti] = frag(a_tok + S * L::TOK_STAGE + 16 * ks * L::TOK_PITCH + ti * 64, L::TOK_PITCH);
+#pragma unroll
+                for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+                    for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(fw[ni], ft[ti], acc[ni][ti]);
+            }
+        }
         store_chunk(std::integral_constant<int, 1 - S>{});
         __syncthreads();
     };
