@@ -22,8 +22,8 @@
 //   * a workgroup is 8 waves = 2 halves of 2 x 2 waves; the halves take alternate contraction chunks
 //     of 64 of the SAME output tile through LDS tiles of their own, and their float32 accumulators
 //     are added through LDS at the end (a fixed order: results do not depend on timing);
-//   * every half keeps two chunks in flight: chunk k + 2 is being fetched into registers while
-//     chunk k is multiplied from LDS and chunk k + 1 waits in the other register set.
+//   * every half keeps three or four chunks in flight: chunk k + depth is being fetched into
+//     registers while chunk k is multiplied from LDS and the chunks between wait in registers.
 // Each wave owns TT x TN MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16); the operand whose index is
 // contiguous in the OUTPUT is the MFMA's row operand, so that each lane stores four consecutive
 // elements.
@@ -33,6 +33,16 @@
 #include "bda_gemm_kernels.hpp"
 
 namespace bda {
+
+// Working instrumentation (compiled only with -DBDA_BWD_TRACE): time stamps of workgroup 5.
+#ifdef BDA_BWD_TRACE
+__device__ unsigned long long bda_bwd_trace[8 * 1024];
+#define BWD_STAMP(tag) do { if (blockIdx.x == 5 && tr_n < 1020) { \
+    const unsigned long long tm_ = __builtin_readcyclecounter(); \
+    if (lane == 0) bda_bwd_trace[wave * 1024 + tr_n] = (tm_ << 8) | (tag); ++tr_n; } } while (0)
+#else
+#define BWD_STAMP(tag) do { } while (0)
+#endif
 
 struct BwdArgs {
     const void* c;    // T x d_c latent
@@ -48,6 +58,21 @@ struct BwdArgs {
     int64_t col_start[kMaxGroups + 1];   // first output column of each group
     int a_off[kMaxGroups];               // basis window start of each group
 };
+
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
+// Register sets of the software pipeline: chunk k + depth is being fetched while chunk k is
+// multiplied (LDS holds chunks k and k + 1).  As many as the register file allows at two waves per
+// SIMD.
+template <int TT, int TN>
+constexpr int bwd_depth() { return TT * TN >= 4 ? 3 : 4; }
 
 // 0/1 fragment (MFMA row operand, one k-step of 16): row i = l31 has a one at k' = i - d.
 template <typename X>
@@ -239,26 +264,40 @@ __global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
         k.jc += 128;
         settle(k);
     };
-    Cursor cur;                           // chunk being multiplied; nxt, ld: one and two iterations ahead
+    Cursor cur;                           // chunk being multiplied
     cur.g = 0;
     cur.q = half;
     cur.jc = 64 * half;
     cur.valid = true;
     enter_group(cur);
     settle(cur);
-    Cursor nxt = cur;
-    advance(nxt);
-    Cursor ld = nxt;
-    advance(ld);
+    Cursor ld = cur;                      // chunk being fetched: D iterations ahead
 
-    // per-lane pieces of the load offsets that do not depend on the chunk
-    uint32_t tok_base[TOK_LOADS];
+    // per-lane pieces of the load offsets that do not depend on the chunk; the rows of C that the
+    // tile's latent columns map to depend on the group's window and are redone when the fetch
+    // cursor enters another group.
+    uint32_t tok_base[TOK_LOADS], wgt_base[WGT_LOADS];
 #pragma unroll
     for (int i = 0; i < TOK_LOADS; ++i) tok_base[i] = (uint32_t)(trow + 32 * i) * g_row_bytes + (uint32_t)(tq * 16);
+    int base_group = -1;
+    auto set_wgt_base = [&](int off) {
+#pragma unroll
+        for (int i = 0; i < WGT_LOADS; ++i) {
+            const int l = l0 + trow + 32 * i;                                 // latent column of this LDS row
+            const int row = l < off ? l : l - p.d_h;                          // its row of C
+            const bool ok = l < p.d_c && (l < off || l >= off + p.d_h);
+            wgt_base[i] = ok ? (uint32_t)row * c_row_bytes + (uint32_t)(tq * 16) : kBadOffset;
+        }
+    };
 
-    u32x4 tok_reg[2][TOK_LOADS], wgt_reg[2][WGT_LOADS];
+    constexpr int D = bwd_depth<TT, TN>();
+    u32x4 tok_reg[D][TOK_LOADS], wgt_reg[D][WGT_LOADS];
     auto load_chunk = [&](auto set, const Cursor& k) {
         constexpr int S = decltype(set)::value;
+        if (k.g != base_group) {          // uniform; first chunk and group changes only
+            set_wgt_base(k.off);
+            base_group = k.g;
+        }
         const int nc = k.start + 64 * k.q;
         const int rem = k.valid ? k.end - nc : 0;             // columns of the group from nc on
         const bool col_ok = tq * 8 < rem;
@@ -271,18 +310,15 @@ __global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
         }
 #pragma unroll
         for (int i = 0; i < WGT_LOADS; ++i) {
-            const int l = l0 + trow + 32 * i;                                 // latent column of this LDS row
-            const int row = l < k.off ? l : l - p.d_h;                        // its row of C
-            const bool ok = col_ok && l < p.d_c && (l < k.off || l >= k.off + p.d_h);
-            uint32_t voff = ok ? (uint32_t)row * c_row_bytes + (uint32_t)(tq * 16) + chunk_bytes : kBadOffset;
+            uint32_t voff = (col_ok && wgt_base[i] != kBadOffset) ? wgt_base[i] + chunk_bytes : kBadOffset;
             asm volatile("" : "+v"(voff));
             wgt_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rC, voff, 0, 0);
         }
     };
-    auto store_chunk = [&](auto set) {
-        constexpr int S = decltype(set)::value;
-        unsigned char* tok_s = lds + S * L::TOK_STAGE;
-        unsigned char* wgt_s = lds + L::WGT_BASE + S * L::WGT_STAGE;
+    auto store_chunk = [&](auto set, auto stage) {
+        constexpr int S = decltype(set)::value, LS = decltype(stage)::value;
+        unsigned char* tok_s = lds + LS * L::TOK_STAGE;
+        unsigned char* wgt_s = lds + L::WGT_BASE + LS * L::WGT_STAGE;
 #pragma unroll
         for (int i = 0; i < TOK_LOADS; ++i) *(u32x4*)(tok_s + lds_off(trow + 32 * i, tq)) = tok_reg[S][i];
 #pragma unroll
@@ -301,14 +337,15 @@ __global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
     const int wgt_rd = L::WGT_BASE + (wn * (32 * TN) + l31) * kRowBytes + lhi * 16;
     const int colm0 = l0 + wn * (32 * TN);           // first latent column of this wave's MFMA tiles
 
-    // an iteration multiplies this half's chunk `cur` from LDS stage S, fetches chunk `ld` into
-    // register set S and moves chunk `nxt` from register set 1 - S to LDS
-    auto iteration = [&](auto set) {
-        constexpr int S = decltype(set)::value;
+    // iteration k multiplies this half's chunk k (`cur`) from LDS stage k % 2, fetches chunk k + D
+    // (`ld`) into register set k % D and moves chunk k + 1 from register set (k + 1) % D to LDS
+    auto iteration = [&](auto set, auto stage) {
+        constexpr int S = decltype(set)::value, LS = decltype(stage)::value;
         load_chunk(set, ld);
+        advance(ld);
         if (cur.valid) {
             const int off = cur.off, jc = cur.jc;
-            bwd_mma_chunk<X, TT, TN>(lds + tok_rd + S * L::TOK_STAGE, lds + wgt_rd + S * L::WGT_STAGE, acc,
+            bwd_mma_chunk<X, TT, TN>(lds + tok_rd + LS * L::TOK_STAGE, lds + wgt_rd + LS * L::WGT_STAGE, acc,
                                      [&](int ks, const u32x4 (&ft)[TT]) {
                 // window rows of Wfull: output columns nc + 16 ks + k' feed latent column off + jk + k'
                 int jk = jc + 16 * ks;
@@ -324,24 +361,24 @@ __global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
                 }
             });
         }
-        store_chunk(std::integral_constant<int, 1 - S>{});
-        cur = nxt;
-        nxt = ld;
-        advance(ld);
+        advance(cur);
+        store_chunk(std::integral_constant<int, (S + 1) % D>{}, std::integral_constant<int, 1 - LS>{});
         __syncthreads();
     };
 
-    {
-        // prologue: chunks `cur` and `nxt` into the two register sets, `cur` on to LDS
-        load_chunk(std::integral_constant<int, 0>{}, cur);
-        load_chunk(std::integral_constant<int, 1>{}, nxt);
-        store_chunk(std::integral_constant<int, 0>{});
-        __syncthreads();
-    }
-    for (int it = 0; it < n_it; it += 2) {
-        iteration(std::integral_constant<int, 0>{});
-        iteration(std::integral_constant<int, 1>{});
-    }
+    // prologue: chunks 0 .. D - 1 into the register sets, chunk 0 on to LDS
+    static_for<D>([&](auto r) {
+        load_chunk(r, ld);
+        advance(ld);
+    });
+    store_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    __syncthreads();
+    constexpr int U = D % 2 == 0 ? D : 2 * D;     // iterations until register set and LDS stage repeat
+    for (int it = 0; it < n_it; it += U)
+        static_for<U>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            iteration(std::integral_constant<int, I % D>{}, std::integral_constant<int, I % 2>{});
+        });
     bwd_reduce_halves<TT, TN>(smem, acc, half, w4, lane);
     if (half == 0) bwd_epilogue<X, OutT, TT, TN>(acc, rD, p.ldo, cols_left, wt, wn, l31, lhi);
 }
@@ -427,33 +464,44 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
     const int n_chunks = (int)((T + 63) >> 6);
     const int n_it = (n_chunks + 1) >> 1;
 
-    u32x4 tok_reg[2][TOK_LOADS], wgt_reg[2][WGT_LOADS];
-    auto load_chunk = [&](auto set, int it) {
+    constexpr int D = bwd_depth<TT, TN>();
+    u32x4 tok_reg[D][TOK_LOADS], wgt_reg[D][WGT_LOADS];
+    // Fetch state of this half: its chunks are 128 tokens apart.  The descriptors move along with a
+    // running base and end with the chunk's last token, so token rows past T (and whole chunks past
+    // the last one) read as zero.  Everything below is scalar and incremental.
+    uint32_t tok_v[TOK_LOADS], wgt_v[WGT_LOADS];      // per-lane offsets inside a chunk (or kBadOffset)
+#pragma unroll
+    for (int i = 0; i < TOK_LOADS; ++i) tok_v[i] = tok_voff == kBadOffset ? kBadOffset : tok_voff + (uint32_t)i * tok_pass;
+#pragma unroll
+    for (int i = 0; i < WGT_LOADS; ++i) wgt_v[i] = wgt_voff == kBadOffset ? kBadOffset : wgt_voff + (uint32_t)i * wgt_pass;
+    const int n_full = (int)(T >> 6), tail_rows = (int)(T & 63);
+    const uint32_t c_full = 63u * (uint32_t)c_pitch + (uint32_t)d_c_bytes;
+    const uint32_t c_tail = tail_rows ? (uint32_t)(tail_rows - 1) * (uint32_t)c_pitch + (uint32_t)d_c_bytes : 0u;
+    const uint32_t g_full = 63u * (uint32_t)g_pitch + (uint32_t)cols_left * 2u;
+    const uint32_t g_tail = tail_rows ? (uint32_t)(tail_rows - 1) * (uint32_t)g_pitch + (uint32_t)cols_left * 2u : 0u;
+    const char* c_ptr = c_base + (int64_t)half * 64 * c_pitch;
+    const char* g_ptr = g_base + (int64_t)half * 64 * g_pitch;
+    const int64_t c_step = 128 * c_pitch, g_step = 128 * g_pitch;
+    int ld_chunk = half;
+    auto load_chunk = [&](auto set) {
         constexpr int S = decltype(set)::value;
-        // descriptors end with the last token, so token rows past T (and whole chunks past the
-        // last one) read as zero
-        const int64_t t = (int64_t)(2 * it + half) * 64;
-        const int64_t rows = T - t > 64 ? 64 : T - t;
-        const int64_t tb = rows > 0 ? t : 0;
-        const __amdgpu_buffer_rsrc_t rA = make_rsrc(c_base + tb * c_pitch, rows > 0 ? (rows - 1) * c_pitch + d_c_bytes : 0);
-        const __amdgpu_buffer_rsrc_t rB = make_rsrc(g_base + tb * g_pitch, rows > 0 ? (rows - 1) * g_pitch + cols_left * 2 : 0);
+        const bool full = ld_chunk < n_full, last = ld_chunk == n_full;
+        const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(c_ptr), 0, (int)(full ? c_full : last ? c_tail : 0u), 0x00020000);
+        const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(g_ptr), 0, (int)(full ? g_full : last ? g_tail : 0u), 0x00020000);
 #pragma unroll
-        for (int i = 0; i < TOK_LOADS; ++i) {
-            uint32_t voff = tok_voff == kBadOffset ? kBadOffset : tok_voff + (uint32_t)i * tok_pass;
-            asm volatile("" : "+v"(voff));                    // one load, not one per branch
-            tok_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rA, voff, 0, 0);
-        }
+        for (int i = 0; i < TOK_LOADS; ++i) tok_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rA, tok_v[i], 0, 0);
 #pragma unroll
-        for (int i = 0; i < WGT_LOADS; ++i) {
-            uint32_t voff = wgt_voff == kBadOffset ? kBadOffset : wgt_voff + (uint32_t)i * wgt_pass;
-            asm volatile("" : "+v"(voff));
-            wgt_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rB, voff, 0, 0);
-        }
+        for (int i = 0; i < WGT_LOADS; ++i) wgt_reg[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rB, wgt_v[i], 0, 0);
+        c_ptr += c_step;
+        g_ptr += g_step;
+        ld_chunk += 2;
     };
-    auto store_chunk = [&](auto set) {
-        constexpr int S = decltype(set)::value;
-        unsigned char* tok_s = lds + S * L::TOK_STAGE + tok_lds;
-        unsigned char* wgt_s = lds + L::WGT_BASE + S * L::WGT_STAGE + wgt_lds;
+    auto store_chunk = [&](auto set, auto stage) {
+        constexpr int S = decltype(set)::value, LS = decltype(stage)::value;
+        unsigned char* tok_s = lds + LS * L::TOK_STAGE + tok_lds;
+        unsigned char* wgt_s = lds + L::WGT_BASE + LS * L::WGT_STAGE + wgt_lds;
 #pragma unroll
         for (int i = 0; i < TOK_LOADS; ++i) *(u32x4*)(tok_s + i * TOK_ROWS_PER_PASS * L::TOK_PITCH) = tok_reg[S][i];
 #pragma unroll
@@ -484,37 +532,46 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
         return (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
     };
 
-    auto iteration = [&](auto set, int it) {
-        constexpr int S = decltype(set)::value;
-        load_chunk(set, it + 2);
+    int tr_n = 0;
+    (void)tr_n;
+    auto iteration = [&](auto set, auto stage, int it) {
+        constexpr int S = decltype(set)::value, LS = decltype(stage)::value;
+        BWD_STAMP(1);
+        load_chunk(set);
+        BWD_STAMP(2);
         if (2 * it + half < n_chunks) {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 u32x4 fw[TN], ft[TT];
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
-                    fw[ni] = frag(a_wgt + S * L::WGT_STAGE + 16 * ks * L::WGT_PITCH + ni * 64, L::WGT_PITCH);
+                    fw[ni] = frag(a_wgt + LS * L::WGT_STAGE + 16 * ks * L::WGT_PITCH + ni * 64, L::WGT_PITCH);
 #pragma unroll
                 for (int ti = 0; ti < TT; ++ti)
-                    ft[ti] = frag(a_tok + S * L::TOK_STAGE + 16 * ks * L::TOK_PITCH + ti * 64, L::TOK_PITCH);
+                    ft[ti] = frag(a_tok + LS * L::TOK_STAGE + 16 * ks * L::TOK_PITCH + ti * 64, L::TOK_PITCH);
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
                     for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(fw[ni], ft[ti], acc[ni][ti]);
             }
         }
-        store_chunk(std::integral_constant<int, 1 - S>{});
+        BWD_STAMP(3);
+        store_chunk(std::integral_constant<int, (S + 1) % D>{}, std::integral_constant<int, 1 - LS>{});
+        BWD_STAMP(4);
         __syncthreads();
+        BWD_STAMP(5);
     };
 
-    load_chunk(std::integral_constant<int, 0>{}, 0);
-    load_chunk(std::integral_constant<int, 1>{}, 1);
-    store_chunk(std::integral_constant<int, 0>{});
+    BWD_STAMP(0);
+    static_for<D>([&](auto r) { load_chunk(r); });
+    store_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     __syncthreads();
-    for (int it = 0; it < n_it; it += 2) {
-        iteration(std::integral_constant<int, 0>{}, it);
-        iteration(std::integral_constant<int, 1>{}, it + 1);
-    }
+    constexpr int U = D % 2 == 0 ? D : 2 * D;     // iterations until register set and LDS stage repeat
+    for (int it = 0; it < n_it; it += U)
+        static_for<U>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            iteration(std::integral_constant<int, I % D>{}, std::integral_constant<int, I % 2>{}, it + I);
+        });
     bwd_reduce_halves<TT, TN>(smem, acc, half, w4, lane);
     if (half == 0) bwd_epilogue<X, OutT, TT, TN>(acc, rD, p.ldo, cols_left, wt, wn, l31, lhi);
 }
