@@ -56,8 +56,9 @@ int launch_sized(BwdArgs& a, int64_t rows, const int64_t* group_cols, int G, hip
         return (int64_t)a.m_tiles * a.n_tiles;
     };
     const int policy = tile_policy();   // 1 forces the 128 x 128 tile (testing hook)
+    // (64 x 128 tiles were measured too: never faster than 64 x 64, which keeps two workgroups on a
+    // compute unit)
     if (grid(128, 128) >= 256 || policy == 1) return launch_mfma<X, OutT, 2, 2, WEIGHT>(a, st);
-    if (grid(64, 128) >= 256) return launch_mfma<X, OutT, 1, 2, WEIGHT>(a, st);
     grid(64, 64);
     return launch_mfma<X, OutT, 1, 1, WEIGHT>(a, st);
 }

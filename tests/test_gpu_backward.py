@@ -98,9 +98,9 @@ def test_backward_general_kernels(dtype):
 
 
 def test_backward_tile_shapes_chosen_by_size():
-    # 64 x 128 tiles: latent gradient with >= 256 such tiles but < 256 tiles of 128 x 128 ...
+    # many 64 x 64 tiles (two per compute unit): 65 x 8 for the latent gradient ...
     _check(4100, 512, 128, [1, 1], [0, 384], wl.F16)
-    # ... and the same for the weight gradient (6 row tiles x 43 column tiles)
+    # ... and 6 x 86 for the weight gradient
     _check(100, 512, 128, [22, 21], [384, 0], wl.BF16)
     # 128 x 128 tiles by size: 65 x 4 latent tiles
     _check(8200, 512, 128, [1], [128], wl.BF16)
