@@ -196,7 +196,8 @@ int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64
 /*
  * Tuning / testing hook: which MFMA tile the fp16/bf16 kernels use.  0 = automatic (default: the
  * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256,
- * 3 = 256 x 256 with the general streaming kernel even where its lean variant would apply.
+ * 3 = 256 x 256 with the general streaming kernel even where its lean variant would apply,
+ * 4 = 128 x 256 with the lean streaming kernel where it applies (else as 2).
  * bda_kv_project_backward honours 1 (128 x 128 output tiles) and treats the rest as automatic.
  * Process-wide; returns the previous policy, or BDA_EINVAL.  Results do not depend on it beyond
  * float32 summation order inside a tile (none: the order over k is the same for every tile shape).

@@ -42,32 +42,54 @@ int launch_mfma(GemmArgs& a, hipStream_t st)
 constexpr int kStreamSK = 64, kStreamNS = 2;
 
 // Streaming kernel; `plain` selects its lean variant (every stage of every tile free of per-lane
-// decisions: see bda_gemm_plain.hpp).
+// decisions: see bda_gemm_plain.hpp), `half_tokens` the lean variant with 128-token tiles.
 template <typename X, typename OutT>
-int launch_stream(GemmArgs& a, bool plain, hipStream_t st)
+int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
 {
-    static std::once_flag once, once_plain;
+    static std::once_flag once, once_plain, once_half;
     constexpr int lds = kStreamNS * (256 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
+    constexpr int lds_half = kStreamNS * (128 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
     auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS, 0>;
-    auto kern_plain = gemm_plain_kernel<X, OutT, 0>;
-    if (int rc = plain ? set_max_lds(kern_plain, lds, once_plain) : set_max_lds(kern, lds, once)) return rc;
+    auto kern_plain = gemm_plain_kernel<X, OutT, 0, 4>;
+    auto kern_half = gemm_plain_kernel<X, OutT, 0, 2>;
+    if (int rc = half_tokens ? set_max_lds(kern_half, lds_half, once_half)
+                 : plain ? set_max_lds(kern_plain, lds, once_plain) : set_max_lds(kern, lds, once)) return rc;
     a.n_super_m = (a.m_tiles + a.sm - 1) / a.sm;
     a.n_super_n = (a.n_tiles + a.sn - 1) / a.sn;
-    a.sn_shift = 0;
-    while ((1 << a.sn_shift) < a.sn) ++a.sn_shift;
     a.dh_magic = a.d_h > 0 ? (((uint64_t)1 << 40) + a.d_h - 1) / a.d_h : 0;
-    {
-        const int64_t total = (int64_t)a.n_super_m * a.n_super_n;
-        a.rounds = (int)((total + kNumXcd - 1) / kNumXcd);
-        for (int x = 0; x < kNumXcd; ++x) {
-            const int64_t first = std::min<int64_t>((int64_t)x * a.rounds, total);
-            a.xcd_q0[x] = (int)(first % a.n_super_m);
-            a.xcd_r0[x] = (int)(first / a.n_super_m);
-            a.xcd_count[x] = (int)std::min<int64_t>(a.rounds, total - first);
+    a.lin_slots = 0;
+    int64_t total = (int64_t)a.n_super_m * a.n_super_n;      // super-tiles
+    int64_t per_die = (total + kNumXcd - 1) / kNumXcd;
+    a.rounds = (int)per_die;
+    if (plain || half_tokens) {
+        // Tile-by-tile order (lean kernel only) where it needs fewer rounds than whole super-tiles:
+        // small grids whose shape does not factor into 8 dies x (sm x sn) slots.
+        const int64_t tiles = (int64_t)a.m_tiles * a.n_tiles;
+        const int64_t run = (tiles + kNumXcd - 1) / kNumXcd;                  // tiles per die
+        const int slots = (int)std::min<int64_t>(kSlotsPerXcd, run);
+        const int64_t lin_rounds = (run + slots - 1) / slots;
+        if (lin_rounds < a.rounds) {
+            a.sm = a.sn = 1;
+            a.n_super_m = a.m_tiles;
+            a.n_super_n = a.n_tiles;
+            a.lin_slots = slots;
+            a.rounds = (int)lin_rounds;
+            total = tiles;
+            per_die = run;
         }
     }
-    if (plain) hipLaunchKernelGGL(kern_plain, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
-    else hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(512), lds, st, a);
+    a.sn_shift = 0;
+    while ((1 << a.sn_shift) < a.sn) ++a.sn_shift;
+    for (int x = 0; x < kNumXcd; ++x) {
+        const int64_t first = std::min<int64_t>((int64_t)x * per_die, total);
+        a.xcd_q0[x] = (int)(first % a.n_super_m);
+        a.xcd_r0[x] = (int)(first / a.n_super_m);
+        a.xcd_count[x] = (int)std::min<int64_t>(per_die, total - first);
+    }
+    const int wgs_per_die = a.lin_slots ? a.lin_slots : a.sm * a.sn;
+    if (half_tokens) hipLaunchKernelGGL(kern_half, dim3(kNumXcd * wgs_per_die), dim3(512), lds_half, st, a);
+    else if (plain) hipLaunchKernelGGL(kern_plain, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
+    else hipLaunchKernelGGL(kern, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
@@ -157,33 +179,41 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_decode<BF16, float>(a, st);
     }
     if (fast && ident_tiles) {
-        // big tiles when they still fill the chip, otherwise 128 x 128 tiles with two workgroups
-        // per compute unit
-        const int64_t mt256 = (a.M + 255) / 256;
+        const int64_t mt256 = (a.M + 255) / 256, mt128 = (a.M + 127) / 128;
         int64_t nt256 = 0;
         for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
         const int policy = g_tile_policy.load();
-        const bool big = policy == 2 || policy == 3 || (policy == 0 && mt256 * nt256 >= 96);   // measured crossover
+        const int n_stage_id = a.ident ? (((a.d_h % 256) == 0 ? 256 : a.d_h) + kStreamSK - 1) / kStreamSK : 0;
+        // Can the streaming kernels take this launch at all, and its lean variant (nothing in any
+        // stage depends on the lane: see bda_gemm_plain.hpp)?
+        bool stream_ok = (a.K + kStreamSK - 1) / kStreamSK + n_stage_id >= kStreamNS && a.d_h < (1 << 16);
+        for (int g = 0; g < G; ++g) stream_ok = stream_ok && group_cols[g] < (1 << 24);   // exact x % d_h by multiplication
+        bool plain = stream_ok && kStreamSK == 64 && kStreamNS == 2 && a.K % 64 == 0 && (!a.ident || a.d_h % 64 == 0)
+                     && a.K / 64 + n_stage_id >= 3 && a.K >= 64 && policy != 3 && policy != 1;
+        for (int g = 0; g < G; ++g) plain = plain && group_cols[g] % 256 == 0 && a.a_off[g] % 64 == 0;
+        // Tile choice.  The lean kernel serves every tile count; its 128-token tile costs 0.53-0.56 of
+        // its 256-token tile per round of tiles (measured), so the smaller tile is taken where it
+        // needs less than 1 / 0.56 times the rounds.  Without the lean kernel: 256 x 256 streaming
+        // tiles from 96 tiles up (measured crossover), else 128 x 128 register-staged tiles.
+        auto rounds_of = [&](int64_t tiles) {
+            const int64_t run = (tiles + kNumXcd - 1) / kNumXcd;
+            return (run + kSlotsPerXcd - 1) / kSlotsPerXcd;
+        };
+        const bool half_tokens = plain && (policy == 4 || (policy == 0 && 0.56 * (double)rounds_of(mt128 * nt256) < (double)rounds_of(mt256 * nt256)));
+        const bool big = plain || policy == 2 || policy == 3 || policy == 4 || (policy == 0 && mt256 * nt256 >= 96);
+        const bool stream = big && stream_ok;
         if (big) {
-            build_tiles(a, G, group_cols, 256, 256);
+            build_tiles(a, G, group_cols, half_tokens ? 128 : 256, 256);
             choose_super(a, kSlotsPerXcd);
             // identity slice: stages of the streaming kernel (the slice of a 256-column tile is the
             // whole window, or the tile's own 256 columns of it when d_h is a multiple of 256)
-            a.n_stage_id = a.ident ? (((a.d_h % 256) == 0 ? 256 : a.d_h) + kStreamSK - 1) / kStreamSK : 0;
+            a.n_stage_id = n_stage_id;
         } else {
             build_tiles(a, G, group_cols, 128, 128);
             choose_super(a, 2 * kSlotsPerXcd);
         }
-        bool stream = big && (a.K + kStreamSK - 1) / kStreamSK + a.n_stage_id >= kStreamNS;
-        for (int g = 0; g < G; ++g) stream = stream && group_cols[g] < (1 << 24);   // exact x % d_h by multiplication
-        stream = stream && a.d_h < (1 << 16);
-        // the lean variant: nothing in any stage depends on the lane (see bda_gemm_plain.hpp)
-        bool plain = stream && kStreamSK == 64 && kStreamNS == 2 && a.K % 64 == 0 && (!a.ident || a.d_h % 64 == 0)
-                     && a.K / 64 + a.n_stage_id >= 3 && a.K >= 64
-                     && g_tile_policy.load() != 3;
-        for (int g = 0; g < G; ++g) plain = plain && group_cols[g] % 256 == 0 && a.a_off[g] % 64 == 0;
 #define BDA_LAUNCH(X, O)                                      \
-    return stream ? launch_stream<X, O>(a, plain, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
+    return stream ? launch_stream<X, O>(a, plain, half_tokens, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
         if (dtype == BDA_F16 && out_dtype == BDA_F16) { BDA_LAUNCH(F16, uint16_t); }
         if (dtype == BDA_F16 && out_dtype == BDA_F32) { BDA_LAUNCH(F16, float); }
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) { BDA_LAUNCH(BF16, uint16_t); }
@@ -220,7 +250,7 @@ using namespace bda;
 extern "C" int bda_set_tile_policy(int policy)
 {
     clear_error();
-    if (policy < 0 || policy > 3) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0 .. 3");
+    if (policy < 0 || policy > 4) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0 .. 4");
     return g_tile_policy.exchange(policy);
 }
 

@@ -44,6 +44,7 @@ struct GemmArgs {
     int rounds;                      // streaming kernel: super-tiles per die, ceil(n_super_m n_super_n / 8)
     int xcd_q0[8], xcd_r0[8];        // streaming kernel: first super-tile of die x (token, column index)
     int xcd_count[8];                // streaming kernel: super-tiles of die x (<= rounds)
+    int lin_slots;                   // lean streaming kernel: > 0 = tile-by-tile order, workgroups per die
     int tile_start[kMaxGroups + 1];  // first column tile of each group
     int64_t col_start[kMaxGroups + 1];  // first output column of each group
     int a_off[kMaxGroups];           // basis window start of each group (k >= a_off -> k + a_skip)

@@ -31,18 +31,18 @@ __device__ __forceinline__ void lds_dma_imm(u32x4 rsrc, uint32_t lds_base, uint3
         : "memory", "m0", "scc");
 }
 
-template <typename X, typename OutT, int DBG = 0>
+template <typename X, typename OutT, int DBG = 0, int TT_ = 4>
 __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 {
     constexpr int SK = 64, WN = 4, NW = 8;
-    constexpr int TT = 4, TN = 2;
-    constexpr int BT = 256, BN = 256;
+    constexpr int TT = TT_, TN = 2;           // TT = 4: 256-token tiles; TT = 2: 128-token tiles
+    constexpr int BT = 64 * TT, BN = 256;
     constexpr int PR = SK / 8, RB = SK * 2, RPI = 64 / PR, KS = SK / 16;
     constexpr int PIT = BT / RPI / NW, PIW = SK / 2 / NW;
     constexpr int TOK_BYTES = BT * RB;
     constexpr int STAGE_BYTES = TOK_BYTES + SK * BN * 2;
     constexpr int STORES = TT * TN * (sizeof(OutT) == 4 ? 4 : 2);
-    static_assert(PIT == 4 && PIW == 4 && STAGE_BYTES == 65536, "layout constants of this variant");
+    static_assert((TT == 4 || TT == 2) && PIT == TT && PIW == 4 && STAGE_BYTES % 1024 == 0, "layout constants of this variant");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     struct {
@@ -50,14 +50,14 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         int64_t lda, ldb, ldd, M;
         int K, n_groups, d_h, a_skip, ident, m_tiles, n_tiles, sm, sn, n_stage_id, n_super_m, n_super_n, sn_shift;
         uint64_t dh_magic;
-        int ts1, ts2, rounds, xq0, xr0, xcount;
+        int ts1, ts2, rounds, xq0, xr0, xcount, lin_slots;
     } q = {p.A, p.B, p.D, p.lda, p.ldb, p.ldd, p.M, p.K, p.n_groups, p.d_h, p.a_skip, p.ident, p.m_tiles, p.n_tiles,
            p.sm, p.sn, p.n_stage_id, p.n_super_m, p.n_super_n, p.sn_shift, p.dh_magic, p.tile_start[1], p.tile_start[2],
-           p.rounds, p.xcd_q0[blockIdx.x % kNumXcd], p.xcd_r0[blockIdx.x % kNumXcd], p.xcd_count[blockIdx.x % kNumXcd]};
+           p.rounds, p.xcd_q0[blockIdx.x % kNumXcd], p.xcd_r0[blockIdx.x % kNumXcd], p.xcd_count[blockIdx.x % kNumXcd], p.lin_slots};
     asm volatile("" : "+s"(q.A), "+s"(q.B), "+s"(q.D), "+s"(q.lda), "+s"(q.ldb), "+s"(q.ldd), "+s"(q.M), "+s"(q.dh_magic));
     asm volatile("" : "+s"(q.K), "+s"(q.n_groups), "+s"(q.d_h), "+s"(q.a_skip), "+s"(q.ident), "+s"(q.m_tiles), "+s"(q.n_tiles),
                  "+s"(q.sm), "+s"(q.sn), "+s"(q.n_stage_id), "+s"(q.n_super_m), "+s"(q.n_super_n), "+s"(q.sn_shift),
-                 "+s"(q.ts1), "+s"(q.ts2), "+s"(q.rounds), "+s"(q.xq0), "+s"(q.xr0), "+s"(q.xcount));
+                 "+s"(q.ts1), "+s"(q.ts2), "+s"(q.rounds), "+s"(q.xq0), "+s"(q.xr0), "+s"(q.xcount), "+s"(q.lin_slots));
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -72,7 +72,8 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     const int S = nk + n_id;
     const int xcd = blockIdx.x % kNumXcd;
     const int slot = blockIdx.x / kNumXcd;
-    const int slot_m = slot >> q.sn_shift, slot_n = slot & (q.sn - 1);
+    const bool linear = q.lin_slots > 0;      // tiles one by one in column-major order (sm = sn = 1 on the host side)
+    const int slot_m = linear ? 0 : slot >> q.sn_shift, slot_n = linear ? 0 : slot & (q.sn - 1);
     auto mod_dh = [&](int x) { return x - (int)(((uint64_t)(uint32_t)x * q.dh_magic) >> 40) * q.d_h; };
 
     // ---- tile set-up (scalar) -----------------------------------------------------------------------
@@ -82,7 +83,12 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     // die's L2 keeps the sn weight tiles and only the token tiles stream, and the column half of the
     // set-up (group lookup, weight descriptor) is done only when the column changes.
     const int n_rounds = q.rounds;
-    int su_q = q.xq0, su_r = q.xr0, su_left = q.xcount;
+    // Small tile grids, where whole super-tiles would leave dies or compute units without work, are
+    // dealt out tile by tile instead: die x takes a contiguous run of the column-major tile order and
+    // its workgroups walk the run with stride lin_slots (the same code with one-tile "super-tiles").
+    const int su_step = linear ? q.lin_slots : 1;
+    int su_q = q.xq0 + (linear ? slot : 0), su_r = q.xr0, su_left = q.xcount - (linear ? slot : 0);
+    while (su_q >= q.n_super_m) { su_q -= q.n_super_m; ++su_r; }
     struct { u32x4 rB; int64_t n0; int cols_left, a_off, j_lo, rel_blk0; bool ok; } col;
     bool col_dirty = true;
     auto setup_cols = [&]() {
@@ -125,9 +131,10 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         t.rB = col.rB;
         if (!valid) t.rB[2] = 0;
         // next super-tile of this die
-        --su_left;
+        su_left -= su_step;
         col_dirty = false;
-        if (++su_q == q.n_super_m) { su_q = 0; ++su_r; col_dirty = true; }
+        su_q += su_step;
+        while (su_q >= q.n_super_m) { su_q -= q.n_super_m; ++su_r; col_dirty = true; }
         return t;
     };
 
@@ -169,9 +176,12 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         const int k0 = k * SK;
         return k < nk ? (uint32_t)(k0 + (k0 >= t.a_off ? q.a_skip : 0)) * 2u : (uint32_t)(t.a_off + t.j_lo + (k - nk) * SK) * 2u;
     };
+    // (a wave's token rows take PIT KiB of a slot's token half, its weight rows 4 KiB of the weight
+    // half; `lds_b` is the slot plus 4 KiB per wave, so the token side steps back for PIT < 4)
+    const uint32_t tok_back = (uint32_t)wave * (uint32_t)(4096 - 1024 * PIT);
     auto tok_load = [&](auto jc, const StreamTile& t, uint32_t lds_b, uint32_t soff) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (!(DBG & 4)) lds_dma_imm<1024 * j>(t.rA, lds_b, vo_tok[j], soff);
+        if constexpr (j < PIT && !(DBG & 4)) lds_dma_imm<1024 * j>(t.rA, lds_b - tok_back, vo_tok[j], soff);
     };
     auto wgt_load = [&](auto jc, u32x4 rW, uint32_t lds_b, uint32_t soff) {
         constexpr int j = decltype(jc)::value;
@@ -180,7 +190,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     auto produce_all = [&](const StreamTile& t, int k, uint32_t slot_b) {
         const uint32_t lds_b = slot_b + wave_lds;
         const uint32_t ts = stage_soff_tok(t, k);
-        tok_load(std::integral_constant<int, 0>{}, t, lds_b, ts);
+        tok_load(std::integral_constant<int, 0>{}, t, lds_b, ts);      // (loads with j >= PIT are no-ops)
         tok_load(std::integral_constant<int, 1>{}, t, lds_b, ts);
         tok_load(std::integral_constant<int, 2>{}, t, lds_b, ts);
         tok_load(std::integral_constant<int, 3>{}, t, lds_b, ts);
@@ -310,7 +320,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         __syncthreads();
         BDA_STAMP(4);
         if (wt == 0) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
-        if constexpr (REG) {
+        if constexpr (REG && TT == 4) {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
             acc[0][2] = mm(fw0[0], ft0[2], acc[0][2]); acc[0][3] = mm(fw0[0], ft0[3], acc[0][3]);
@@ -319,6 +329,11 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw0[1], ft0[2], acc[1][2]); acc[1][3] = mm(fw0[1], ft0[3], acc[1][3]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+        } else if constexpr (REG) {
+            acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]); acc[1][1] = mm(fw0[1], ft0[1], acc[1][1]);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
         } else {
             mma_identity(idf, jc + 32, ft0);
             tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts);
@@ -330,7 +345,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         // first fragments of the next stage, out of the other slot
         if (next_regular) read_w(0, fw0);
         read_t(0, ft0);
-        if constexpr (REG) {
+        if constexpr (REG && TT == 4) {
             acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]); acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws); __builtin_amdgcn_sched_barrier(0);
             acc[0][2] = mm(fw1[0], ft1[2], acc[0][2]); acc[0][3] = mm(fw1[0], ft1[3], acc[0][3]);
@@ -339,6 +354,15 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw1[1], ft1[2], acc[1][2]); acc[1][3] = mm(fw1[1], ft1[3], acc[1][3]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step); __builtin_amdgcn_sched_barrier(0);
+        } else if constexpr (REG) {
+            acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws); __builtin_amdgcn_sched_barrier(0);
+            acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 1>{}, rW, lds_b, ws + wgt_step); __builtin_amdgcn_sched_barrier(0);
+            acc[1][0] = mm(fw1[1], ft1[0], acc[1][0]);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step); __builtin_amdgcn_sched_barrier(0);
+            acc[1][1] = mm(fw1[1], ft1[1], acc[1][1]);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step); __builtin_amdgcn_sched_barrier(0);
         } else {
             mma_identity(idf, jc + 48, ft1);
             wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws);
@@ -346,7 +370,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step);
             wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step);
         }
-        slot_b ^= (uint32_t)STAGE_BYTES;
+        slot_b = (uint32_t)STAGE_BYTES - slot_b;
     };
 
     BDA_STAMP(0);

@@ -79,19 +79,19 @@ def test_kv_medium_ragged(policy, dtype, offs):
     _run_kv_case(w, offs, policy=policy)
 
 
-@pytest.mark.parametrize("policy", [2, 3])
+@pytest.mark.parametrize("policy", [2, 3, 4])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.F16, wl.F32)])
 @pytest.mark.parametrize("offs", [[0, 0], [384, 384], [64, 192]])
 def test_kv_lean_and_general_streaming_kernels(policy, dtype, out_dtype, offs):
     """Full 256-column tiles and windows on multiples of 64: policy 2 runs the lean streaming kernel,
-    policy 3 forces the general one on the same launch; 700 tokens = three token tiles per workgroup
-    column, the last one ragged."""
+    policy 3 forces the general one on the same launch, policy 4 the lean kernel with 128-token tiles;
+    700 tokens = three (six) token tiles per workgroup column, the last one ragged."""
     w = wl.custom_kv_workload("lean", T=700, d_c=512, d_h=128, H=[4, 2], std=0.02, rms_norm=True,
                               dtype=dtype, seed=12)
     _run_kv_case(w, offs, out_dtype=out_dtype, policy=policy)
 
 
-@pytest.mark.parametrize("policy", [2, 3])
+@pytest.mark.parametrize("policy", [2, 3, 4])
 def test_dense_many_stages_streaming(policy):
     """A long contraction (K = 1024: 16 stages per tile, no identity slice) through both streaming kernels."""
     rng = np.random.default_rng(13)
@@ -166,7 +166,7 @@ def test_zero_C_copies_basis_slice_bit_exactly(dtype):
                               dtype=dtype, seed=17)
     offs = [64, 384]
     C_stored, _ = wl.to_storage(np.zeros((384, w.N)), dtype)
-    for policy in (1, 2):
+    for policy in (1, 2, 4):
         bda.bda_set_tile_policy(policy)
         got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, dtype)
         bda.bda_set_tile_policy(0)

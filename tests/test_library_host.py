@@ -186,7 +186,7 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert bwd(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None) == 0
     assert lib.bda_dense_project(fake, 64, 4, 64, fake, 8, 32, fake, 32, 1, 1, None) == -1
     assert lib.bda_lowrank_linear(fake, 64, 4, 64, 8, 40, 3, fake, fake, fake, 40, 1, None) == -1
-    assert lib.bda_set_tile_policy(7) == -1
+    assert lib.bda_set_tile_policy(7) == -1 and lib.bda_set_tile_policy(-1) == -1
     assert lib.bda_set_tile_policy(0) >= 0
 
 
