@@ -51,16 +51,13 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         int K, n_groups, d_h, a_skip, ident, m_tiles, n_tiles, sm, sn, n_stage_id, n_super_m, n_super_n, sn_shift;
         uint64_t dh_magic;
         int ts1, ts2, rounds, xq0, xr0, xcount, lin_slots;
-        int cs1, cs2, off0, off1;             // group tables of the first two groups (column starts fit 24 bits here)
     } q = {p.A, p.B, p.D, p.lda, p.ldb, p.ldd, p.M, p.K, p.n_groups, p.d_h, p.a_skip, p.ident, p.m_tiles, p.n_tiles,
            p.sm, p.sn, p.n_stage_id, p.n_super_m, p.n_super_n, p.sn_shift, p.dh_magic, p.tile_start[1], p.tile_start[2],
-           p.rounds, p.xcd_q0[blockIdx.x % kNumXcd], p.xcd_r0[blockIdx.x % kNumXcd], p.xcd_count[blockIdx.x % kNumXcd], p.lin_slots,
-           (int)p.col_start[1], (int)p.col_start[2], p.a_off[0], p.a_off[1]};
+           p.rounds, p.xcd_q0[blockIdx.x % kNumXcd], p.xcd_r0[blockIdx.x % kNumXcd], p.xcd_count[blockIdx.x % kNumXcd], p.lin_slots};
     asm volatile("" : "+s"(q.A), "+s"(q.B), "+s"(q.D), "+s"(q.lda), "+s"(q.ldb), "+s"(q.ldd), "+s"(q.M), "+s"(q.dh_magic));
     asm volatile("" : "+s"(q.K), "+s"(q.n_groups), "+s"(q.d_h), "+s"(q.a_skip), "+s"(q.ident), "+s"(q.m_tiles), "+s"(q.n_tiles),
                  "+s"(q.sm), "+s"(q.sn), "+s"(q.n_stage_id), "+s"(q.n_super_m), "+s"(q.n_super_n), "+s"(q.sn_shift),
                  "+s"(q.ts1), "+s"(q.ts2), "+s"(q.rounds), "+s"(q.xq0), "+s"(q.xr0), "+s"(q.xcount), "+s"(q.lin_slots));
-    // (the group tables are not pinned: they are read in one batch wherever a column set-up needs them)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -97,27 +94,12 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     auto setup_cols = [&]() {
         const int nt = su_r * q.sn + slot_n;
         col.ok = nt < q.n_tiles;
-        // group of the column tile: one or two groups (K and V blocks) from registers, more from the
-        // argument tables
-        int g_tile0, g_col0, g_col1, g_off;
-        if (q.n_groups <= 2) {
-            const bool second = q.n_groups == 2 && nt >= q.ts1;
-            g_tile0 = second ? q.ts1 : 0;
-            g_col0 = second ? q.cs1 : 0;
-            g_col1 = second ? q.cs2 : q.cs1;
-            g_off = second ? q.off1 : q.off0;
-        } else {
-            int g = 0;
-            while (g + 1 < q.n_groups && nt >= p.tile_start[g + 1]) ++g;
-            g_tile0 = p.tile_start[g];
-            g_col0 = (int)p.col_start[g];
-            g_col1 = (int)p.col_start[g + 1];
-            g_off = p.a_off[g];
-        }
-        g_tile0 = __builtin_amdgcn_readfirstlane(g_tile0);
-        g_col0 = __builtin_amdgcn_readfirstlane(g_col0);
-        g_col1 = __builtin_amdgcn_readfirstlane(g_col1);
-        g_off = __builtin_amdgcn_readfirstlane(g_off);
+        int g = 0;
+        if (q.n_groups <= 2) g = (q.n_groups == 2 && nt >= q.ts1) ? 1 : 0;
+        else if (nt >= q.ts1) { g = 1; while (g + 1 < q.n_groups && nt >= p.tile_start[g + 1]) ++g; }
+        // (column starts fit 24 bits here; the three table reads go out together)
+        const int g_tile0 = g == 0 ? 0 : g == 1 ? q.ts1 : p.tile_start[g];
+        const int g_col0 = (int)p.col_start[g], g_col1 = (int)p.col_start[g + 1], g_off = p.a_off[g];
         const int rel0 = col.ok ? (nt - g_tile0) * BN : 0;
         col.n0 = col.ok ? g_col0 + rel0 : 0;
         const int left = g_col1 - (int)col.n0;
