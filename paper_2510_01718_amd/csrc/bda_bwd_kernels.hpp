@@ -389,13 +389,18 @@ __global__ __launch_bounds__(512) void bwd_latent_kernel(const BwdArgs p)
 // is the slow index of both in memory, so both tiles are copied to LDS as they are -- one LDS row
 // per token, coalesced on both sides -- and the fragments are read with the transposing LDS read
 // (ds_read_b64_tr_b16): each lane names four consecutive columns of one token row and receives
-// four consecutive tokens of one column.  Rows are padded by 32 bytes, so that the four token rows
-// one such read touches lie on different banks.
+// four consecutive tokens of one column.  Rows are not padded; the 16-byte pieces of a row are XOR-
+// swizzled by the row number so that the four token rows one such read touches (64 bytes each) fall
+// into different quarters of the 256-byte bank line, while a row's pieces stay within the row (the
+// copies into LDS write whole rows).
 // ---------------------------------------------------------------------------------------------
 template <int TT, int TN>
 struct BwdWeightLds {
     static constexpr int BT = 64 * TT, BN = 64 * TN;
-    static constexpr int TOK_PITCH = BT * 2 + 32, WGT_PITCH = BN * 2 + 32;   // bytes per token row
+    static constexpr int TOK_PITCH = BT * 2, WGT_PITCH = BN * 2;             // bytes per token row
+    // piece p of row r sits at p ^ swz(r): 128-byte rows pair up in a bank line, so the pair number
+    // picks the half; 256-byte rows fill one, so the row number picks the quarter
+    static __device__ __forceinline__ int swz(int pitch, int r) { return pitch == 128 ? ((r >> 1) & 1) * 4 : (r & 3) * 4; }
     static constexpr int TOK_STAGE = 64 * TOK_PITCH, WGT_STAGE = 64 * WGT_PITCH;
     static constexpr int WGT_BASE = 2 * TOK_STAGE;
     static constexpr int HALF = 2 * (TOK_STAGE + WGT_STAGE);
@@ -452,12 +457,12 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
         const int ia = i0 + piece * 8;                              // row of C
         const int col = ia < a_off ? ia : ia + p.d_h;               // its latent column
         tok_voff = piece * 8 < rows_left ? (uint32_t)row * (uint32_t)c_pitch + (uint32_t)col * 2u : kBadOffset;
-        tok_lds = (uint32_t)(row * L::TOK_PITCH + piece * 16);
+        tok_lds = (uint32_t)(row * L::TOK_PITCH + ((piece ^ L::swz(L::TOK_PITCH, row)) * 16));
     }
     {
         const int piece = tid % WGT_PER_ROW, row = tid / WGT_PER_ROW;
         wgt_voff = piece * 8 < cols_left ? (uint32_t)row * (uint32_t)g_pitch + (uint32_t)piece * 16u : kBadOffset;
-        wgt_lds = (uint32_t)(row * L::WGT_PITCH + piece * 16);
+        wgt_lds = (uint32_t)(row * L::WGT_PITCH + ((piece ^ L::swz(L::WGT_PITCH, row)) * 16));
     }
     const uint32_t tok_pass = (uint32_t)TOK_ROWS_PER_PASS * (uint32_t)c_pitch;
     const uint32_t wgt_pass = (uint32_t)WGT_ROWS_PER_PASS * (uint32_t)g_pitch;
@@ -523,8 +528,19 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8)lds;
     const int c_s = lane & 15, c_q = lane >> 4;
     const int fr_row = 8 * (c_q >> 1) + (c_s >> 2), fr_col = 16 * (c_q & 1) + 4 * (c_s & 3);
-    const uint32_t a_tok = lds0 + (uint32_t)(fr_row * L::TOK_PITCH + (wt * (32 * TT) + fr_col) * 2);
-    const uint32_t a_wgt = lds0 + (uint32_t)(L::WGT_BASE + fr_row * L::WGT_PITCH + (wn * (32 * TN) + fr_col) * 2);
+    // (the rows a lane reads differ by multiples of 4, and the passes of a copy by 16 or 32 rows, so
+    // the swizzle is a constant of the lane on both sides)
+    uint32_t a_tok[TT], a_wgt[TN];
+#pragma unroll
+    for (int ti = 0; ti < TT; ++ti) {
+        const int cb = (wt * (32 * TT) + 32 * ti + fr_col) * 2;
+        a_tok[ti] = lds0 + (uint32_t)(fr_row * L::TOK_PITCH + (((cb >> 4) ^ L::swz(L::TOK_PITCH, fr_row)) << 4) + (cb & 15));
+    }
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni) {
+        const int cb = (wn * (32 * TN) + 32 * ni + fr_col) * 2;
+        a_wgt[ni] = lds0 + (uint32_t)(L::WGT_BASE + fr_row * L::WGT_PITCH + (((cb >> 4) ^ L::swz(L::WGT_PITCH, fr_row)) << 4) + (cb & 15));
+    }
     auto frag = [&](uint32_t addr, int pitch) {
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(uintptr_t)addr);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(uintptr_t)(addr + 4 * pitch));
@@ -545,10 +561,10 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
                 u32x4 fw[TN], ft[TT];
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
-                    fw[ni] = frag(a_wgt + LS * L::WGT_STAGE + 16 * ks * L::WGT_PITCH + ni * 64, L::WGT_PITCH);
+                    fw[ni] = frag(a_wgt[ni] + LS * L::WGT_STAGE + 16 * ks * L::WGT_PITCH, L::WGT_PITCH);
 #pragma unroll
                 for (int ti = 0; ti < TT; ++ti)
-                    ft[ti] = frag(a_tok + LS * L::TOK_STAGE + 16 * ks * L::TOK_PITCH + ti * 64, L::TOK_PITCH);
+                    ft[ti] = frag(a_tok[ti] + LS * L::TOK_STAGE + 16 * ks * L::TOK_PITCH, L::TOK_PITCH);
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
