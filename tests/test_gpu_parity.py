@@ -91,6 +91,32 @@ def test_kv_lean_and_general_streaming_kernels(policy, dtype, out_dtype, offs):
     _run_kv_case(w, offs, out_dtype=out_dtype, policy=policy)
 
 
+@pytest.mark.parametrize("policy", [2, 4])
+def test_kv_lean_three_groups(policy):
+    """Three groups with different windows through the lean kernel (group look-up beyond the two
+    register-held groups)."""
+    w = wl.custom_kv_workload("lean3", T=300, d_c=512, d_h=128, H=[2, 4, 2], std=0.02, rms_norm=True,
+                              dtype=wl.BF16, seed=21)
+    _run_kv_case(w, [0, 64, 384], policy=policy)
+
+
+def test_kv_lean_tile_by_tile_order_two_rounds():
+    """17 x 25 tiles of 128 x 256: whole super-tiles would need three rounds, so the tiles are dealt
+    out one by one (54 per die, two rounds, the last die's run shorter); ragged last token tile."""
+    w = wl.custom_kv_workload("linear2", T=2100, d_c=512, d_h=128, H=[26, 24], std=0.02, rms_norm=True,
+                              dtype=wl.F16, seed=22)
+    _run_kv_case(w, [0, 384], policy=4)
+
+
+@pytest.mark.parametrize("T", [100, 1300, 1536])
+def test_kv_lean_automatic_tile_choice(T):
+    """Automatic policy on the V2-Lite shape at token counts that select 128-token tiles
+    (tile-by-tile order at 1536: 12 x 16 tiles)."""
+    w = wl.custom_kv_workload("auto", T=T, d_c=512, d_h=128, H=[16, 16], std=0.02, rms_norm=True,
+                              dtype=wl.F16, seed=23)
+    _run_kv_case(w, [0, 0])
+
+
 @pytest.mark.parametrize("policy", [2, 3, 4])
 def test_dense_many_stages_streaming(policy):
     """A long contraction (K = 1024: 16 stages per tile, no identity slice) through both streaming kernels."""
