@@ -1,7 +1,9 @@
 // Lean variant of the streaming MFMA GEMM (bda_gemm_stream.hpp) for launches in which every stage
-// of every tile is "plain": K, the basis windows and the head width are multiples of the stage
-// length 64, and every group's width is a multiple of the 256-column tile.  Then no stage needs a
-// per-lane decision, and everything that changes from stage to stage is uniform:
+// of every tile is "plain": K and the head width are multiples of the stage length 64, the basis
+// windows start on multiples of 8 and every group's width is a multiple of the 256-column tile.
+// Then no stage needs a per-lane decision (but for the one stage per tile that holds the start of a
+// window off the 64 grid, which shifts some lanes' offsets by the window's width), and everything
+// that changes from stage to stage is uniform:
 //   * the vector offset of each of a wave's eight loads never changes; the stage's column / row
 //     offset travels in the load's scalar offset;
 //   * the LDS addresses of the fragment reads flip between the two stage slots with one XOR each.
@@ -182,9 +184,27 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     // (a wave's token rows take PIT KiB of a slot's token half, its weight rows 4 KiB of the weight
     // half; `lds_b` is the slot plus 4 KiB per wave, so the token side steps back for PIT < 4)
     const uint32_t tok_back = (uint32_t)wave * (uint32_t)(4096 - 1024 * PIT);
-    auto tok_load = [&](auto jc, const StreamTile& t, uint32_t lds_b, uint32_t soff) {
+    // Per-lane token offsets of stage k of tile t: the launch constants, except in the one stage
+    // that holds the start of a basis window that is not a multiple of the stage length: there the
+    // 16-byte pieces at or past the window's start skip the window (uniform branch, once per tile).
+    const uint32_t skip_bytes = (uint32_t)q.a_skip * 2u;
+    auto tok_voffs = [&](const StreamTile& t, int k, uint32_t (&vt)[PIT]) {
+#pragma unroll
+        for (int j = 0; j < PIT; ++j) vt[j] = vo_tok[j];
+        const int e = t.a_off & (SK - 1);
+        if (e != 0 && k == t.a_off / SK && k < nk) {
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+#pragma unroll
+            for (int j = 0; j < PIT; ++j) {
+                const int x = ((ln % PR) ^ tok_swz<SK>((ln / PR + RPI * j) & 15)) * 8;   // first k of the lane's piece, within the stage
+                if (x >= e) vt[j] += skip_bytes;
+            }
+        }
+    };
+    auto tok_load = [&](auto jc, const StreamTile& t, uint32_t lds_b, uint32_t soff, const uint32_t (&vt)[PIT]) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (j < PIT && !(DBG & 4)) lds_dma_imm<1024 * j>(t.rA, lds_b - tok_back, vo_tok[j], soff);
+        if constexpr (j < PIT && !(DBG & 4)) lds_dma_imm<1024 * j>(t.rA, lds_b - tok_back, vt[j], soff);
     };
     auto wgt_load = [&](auto jc, u32x4 rW, uint32_t lds_b, uint32_t soff) {
         constexpr int j = decltype(jc)::value;
@@ -193,10 +213,12 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     auto produce_all = [&](const StreamTile& t, int k, uint32_t slot_b) {
         const uint32_t lds_b = slot_b + wave_lds;
         const uint32_t ts = stage_soff_tok(t, k);
-        tok_load(std::integral_constant<int, 0>{}, t, lds_b, ts);      // (loads with j >= PIT are no-ops)
-        tok_load(std::integral_constant<int, 1>{}, t, lds_b, ts);
-        tok_load(std::integral_constant<int, 2>{}, t, lds_b, ts);
-        tok_load(std::integral_constant<int, 3>{}, t, lds_b, ts);
+        uint32_t vt[PIT];
+        tok_voffs(t, k, vt);
+        tok_load(std::integral_constant<int, 0>{}, t, lds_b, ts, vt);      // (loads with j >= PIT are no-ops)
+        tok_load(std::integral_constant<int, 1>{}, t, lds_b, ts, vt);
+        tok_load(std::integral_constant<int, 2>{}, t, lds_b, ts, vt);
+        tok_load(std::integral_constant<int, 3>{}, t, lds_b, ts, vt);
         u32x4 rW = t.rB;
         if (k >= nk) rW[2] = 0;
         const uint32_t ws = k < nk ? (uint32_t)(k * SK) * wgt_row_bytes : 0u;
@@ -314,6 +336,8 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         // uniform part of the requests that follow the barrier
         const uint32_t lds_b = slot_b + wave_lds;
         const uint32_t ts = stage_soff_tok(pt, pk);
+        uint32_t vt[PIT];
+        tok_voffs(pt, pk, vt);
         u32x4 rW = pt.rB;
         if (pk >= nk) rW[2] = 0;              // identity stage: the weight half of the slot is filled with zeros
         const uint32_t ws = pk < nk ? (uint32_t)(pk * SK) * wgt_row_bytes : 0u;
@@ -325,24 +349,24 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         if (wt == 0) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
         if constexpr (REG && TT == 4) {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
-            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[0][2] = mm(fw0[0], ft0[2], acc[0][2]); acc[0][3] = mm(fw0[0], ft0[3], acc[0][3]);
-            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]); acc[1][1] = mm(fw0[1], ft0[1], acc[1][1]);
-            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw0[1], ft0[2], acc[1][2]); acc[1][3] = mm(fw0[1], ft0[3], acc[1][3]);
-            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
         } else if constexpr (REG) {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
-            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]); acc[1][1] = mm(fw0[1], ft0[1], acc[1][1]);
-            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
         } else {
             mma_identity(idf, jc + 32, ft0);
-            tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts);
-            tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts);
-            tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts);
-            tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts);
+            tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt);
+            tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt);
+            tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt);
+            tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt);
         }
         BDA_STAMP(5);
         // first fragments of the next stage, out of the other slot

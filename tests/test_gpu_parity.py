@@ -81,9 +81,10 @@ def test_kv_medium_ragged(policy, dtype, offs):
 
 @pytest.mark.parametrize("policy", [2, 3, 4])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.F16, wl.F32)])
-@pytest.mark.parametrize("offs", [[0, 0], [384, 384], [64, 192]])
+@pytest.mark.parametrize("offs", [[0, 0], [384, 384], [64, 192], [16, 208], [8, 376], [120, 72]])
 def test_kv_lean_and_general_streaming_kernels(policy, dtype, out_dtype, offs):
-    """Full 256-column tiles and windows on multiples of 64: policy 2 runs the lean streaming kernel,
+    """Full 256-column tiles, windows on and off the multiples of 64 (the stage that holds a window's
+    start then shifts part of its lanes): policy 2 runs the lean streaming kernel,
     policy 3 forces the general one on the same launch, policy 4 the lean kernel with 128-token tiles;
     700 tokens = three (six) token tiles per workgroup column, the last one ragged."""
     w = wl.custom_kv_workload("lean", T=700, d_c=512, d_h=128, H=[4, 2], std=0.02, rms_norm=True,
@@ -190,9 +191,8 @@ def test_kv_general_kernel_for_unaligned_shapes():
 def test_zero_C_copies_basis_slice_bit_exactly(dtype):
     w = wl.custom_kv_workload("copy", T=200, d_c=512, d_h=128, H=[2, 2], std=0.02, rms_norm=True,
                               dtype=dtype, seed=17)
-    offs = [64, 384]
     C_stored, _ = wl.to_storage(np.zeros((384, w.N)), dtype)
-    for policy in (1, 2, 4):
+    for policy, offs in ((1, [64, 384]), (2, [64, 384]), (4, [64, 384]), (2, [40, 376]), (4, [8, 200])):
         bda.bda_set_tile_policy(policy)
         got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, dtype)
         bda.bda_set_tile_policy(0)
