@@ -418,6 +418,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     BDA_STAMP(15);
     read_w(0, fw0);
     read_t(0, ft0);
+    BDA_STAMP(16);
 
     const std::true_type REGULAR{};
     const std::false_type IDENTITY{};
@@ -427,6 +428,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll 1
     for (int round = 0; round < n_rounds; ++round) {
         const StreamTile nxt = setup();
+        BDA_STAMP(17);
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {      // d_h >= 64 is a multiple of 64 and rel_blk0 < d_h
             rel_blk[ni] = cur.rel_blk0 + 32 * ni;
