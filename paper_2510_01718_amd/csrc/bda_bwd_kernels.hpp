@@ -122,10 +122,8 @@ __device__ __forceinline__ void bwd_epilogue(const f32x16 (&acc)[TN][TT], __amdg
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, off, 0, 0);
                 } else {
                     u32x2 v;
-                    v[0] = (uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 0]) |
-                           ((uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 1]) << 16);
-                    v[1] = (uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 2]) |
-                           ((uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 3]) << 16);
+                    v[0] = X::pack2(acc[ni][ti][rg * 4 + 0], acc[ni][ti][rg * 4 + 1]);
+                    v[1] = X::pack2(acc[ni][ti][rg * 4 + 2], acc[ni][ti][rg * 4 + 3]);
                     __builtin_amdgcn_raw_buffer_store_b64(v, rD, off, 0, 0);
                 }
             }

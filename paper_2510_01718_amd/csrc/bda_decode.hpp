@@ -149,8 +149,8 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, off, 0, 0);
         } else {
             u32x2 o;
-            o[0] = (uint32_t)X::from_f32(v[0]) | ((uint32_t)X::from_f32(v[1]) << 16);
-            o[1] = (uint32_t)X::from_f32(v[2]) | ((uint32_t)X::from_f32(v[3]) << 16);
+            o[0] = X::pack2(v[0], v[1]);
+            o[1] = X::pack2(v[2], v[3]);
             __builtin_amdgcn_raw_buffer_store_b64(o, rD, off, 0, 0);
         }
     }

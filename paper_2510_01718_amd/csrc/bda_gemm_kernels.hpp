@@ -56,6 +56,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 struct F16 {
     typedef _Float16 elem;
@@ -66,6 +69,12 @@ struct F16 {
     }
     static __device__ __forceinline__ float to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
     static __device__ __forceinline__ uint16_t from_f32(float v) { return __builtin_bit_cast(uint16_t, (_Float16)v); }
+    // two values rounded (nearest even) and packed, lo in bits 0..15: one v_cvt_pk_f16_f32
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        const f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
 };
 
 struct BF16 {
@@ -83,6 +92,12 @@ struct BF16 {
         if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
         u += 0x7fffu + ((u >> 16) & 1u);
         return (uint16_t)(u >> 16);
+    }
+    // two values rounded (nearest even) and packed, lo in bits 0..15: one v_cvt_pk_bf16_f32
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        const f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
     }
 };
 
@@ -358,10 +373,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs p)
                         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, off, 0, 0);
                     } else {
                         u32x2 v;
-                        v[0] = (uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 0]) |
-                               ((uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 1]) << 16);
-                        v[1] = (uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 2]) |
-                               ((uint32_t)X::from_f32(acc[ni][ti][rg * 4 + 3]) << 16);
+                        v[0] = X::pack2(acc[ni][ti][rg * 4 + 0], acc[ni][ti][rg * 4 + 1]);
+                        v[1] = X::pack2(acc[ni][ti][rg * 4 + 2], acc[ni][ti][rg * 4 + 3]);
                         __builtin_amdgcn_raw_buffer_store_b64(v, rD, off, 0, 0);
                     }
                 }

@@ -653,10 +653,8 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                             uint32_t xv[2], yv[2];
 #pragma unroll
                             for (int q = 0; q < 2; ++q) {
-                                xv[q] = (uint32_t)X::from_f32(acc[ni][ti][(2 * pr) * 4 + 2 * q]) |
-                                        ((uint32_t)X::from_f32(acc[ni][ti][(2 * pr) * 4 + 2 * q + 1]) << 16);
-                                yv[q] = (uint32_t)X::from_f32(acc[ni][ti][(2 * pr + 1) * 4 + 2 * q]) |
-                                        ((uint32_t)X::from_f32(acc[ni][ti][(2 * pr + 1) * 4 + 2 * q + 1]) << 16);
+                                xv[q] = X::pack2(acc[ni][ti][(2 * pr) * 4 + 2 * q], acc[ni][ti][(2 * pr) * 4 + 2 * q + 1]);
+                                yv[q] = X::pack2(acc[ni][ti][(2 * pr + 1) * 4 + 2 * q], acc[ni][ti][(2 * pr + 1) * 4 + 2 * q + 1]);
                             }
                             const u32x2 s0 = __builtin_amdgcn_permlane32_swap(xv[0], yv[0], false, false);
                             const u32x2 s1 = __builtin_amdgcn_permlane32_swap(xv[1], yv[1], false, false);
