@@ -239,12 +239,15 @@ def main() -> int:
                                                                     gc_b, d_c, None, N, w.dtype, w.dtype, s), args.steps, args.warmup)
         t_gC = bench_small(lambda i, s: bda.bda_kv_project_backward(c_bufs[i % R], d_c, o_bufs[i % R], N, None, N, T, d_c, d_h, H, offs,
                                                                     None, d_c, gC_b, N, w.dtype, w.dtype, s), args.steps, args.warmup)
+        t_both = bench_small(lambda i, s: bda.bda_kv_project_backward(c_bufs[i % R], d_c, o_bufs[i % R], N, C_d, N, T, d_c, d_h, H, offs,
+                                                                      gc_b, d_c, gC_b, N, w.dtype, w.dtype, s), args.steps, args.warmup)
         extra["backward_v2lite_T4096"] = {
             "grad_c_us": t_gc * 1e6, "grad_c_tflops": flops / t_gc / 1e12,
             "grad_C_us": t_gC * 1e6, "grad_C_tflops": flops / t_gC / 1e12,
-            "vs_forward": (t_gc + t_gC) / kernel_s}
+            "both_one_call_us": t_both * 1e6, "both_tflops": 2 * flops / t_both / 1e12,
+            "vs_forward": t_both / kernel_s}
         log(f"backward: grad_c {t_gc * 1e6:.1f} us ({flops / t_gc / 1e12:.0f} TFLOP/s), grad_C {t_gC * 1e6:.1f} us "
-            f"({flops / t_gC / 1e12:.0f} TFLOP/s)")
+            f"({flops / t_gC / 1e12:.0f} TFLOP/s), both in one call {t_both * 1e6:.1f} us ({2 * flops / t_both / 1e12:.0f} TFLOP/s)")
         del gc_b, gC_b
         # the main measurement once more, after the other measurements (clock / power state check)
         t_again = bench_small(lambda i, s: main_step.fn(i, s), args.steps, args.warmup)
