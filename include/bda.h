@@ -204,6 +204,43 @@ int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64
  */
 int bda_set_tile_policy(int policy);
 
+/*
+ * Launch description: which kernel, tile shape and schedule bda_kv_project / bda_dense_project
+ * would use for a problem, from the same validation and tile choice as the real calls.  Runs on the
+ * host only (no GPU needed, nothing is launched); pointers are assumed 16-byte aligned.  For
+ * tests, tuning and documentation of the launch-shape rules; honours bda_set_tile_policy.
+ */
+typedef enum {
+    BDA_KERNEL_NONE = 0,    /* nothing to launch (T = 0) */
+    BDA_KERNEL_GENERAL = 1, /* any type / shape / alignment: 64 x 64 tiles, float32 FMA */
+    BDA_KERNEL_MFMA = 2,    /* register-staged MFMA kernel, 128 x 128 or 256 x 256 tiles */
+    BDA_KERNEL_STREAM = 3,  /* streaming MFMA kernel (LDS DMA ring), general variant */
+    BDA_KERNEL_LEAN = 4,    /* streaming MFMA kernel, lean variant (256- or 128-token tiles) */
+    BDA_KERNEL_DECODE = 5   /* T <= 64: weight-streaming kernel, 32-column slices */
+} bda_kernel_id;
+
+typedef struct {
+    int kernel;        /* bda_kernel_id */
+    int tile_tokens;   /* output tile: tokens x columns */
+    int tile_columns;
+    int token_tiles;   /* tile grid */
+    int column_tiles;
+    int workgroups;    /* grid size */
+    int threads;       /* per workgroup */
+    int lds_bytes;     /* per workgroup */
+    int rounds;        /* tiles (or super-tiles) a persistent workgroup works through at most */
+    int tile_by_tile;  /* 1: dies take runs of single tiles; 0: super-tiles of super_m x super_n tiles */
+    int super_m;
+    int super_n;
+} bda_launch_plan;
+
+int bda_kv_project_plan(int64_t T, int d_c, int d_h, int G, const int* H, const int* basis_offset,
+                        int64_t ldc, int64_t ldC, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
+                        bda_launch_plan* plan);
+
+int bda_dense_project_plan(int64_t T, int d_c, int64_t N, int64_t ldc, int64_t ldW, int64_t ld_out,
+                           bda_dtype dtype, bda_dtype out_dtype, bda_launch_plan* plan);
+
 /* Message of the last failing call on this thread; never NULL ("" if none). */
 const char* bda_last_error(void);
 

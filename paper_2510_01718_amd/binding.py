@@ -19,10 +19,23 @@ BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
 EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_kv_project", "bda_dense_project",
-           "bda_lowrank_linear", "bda_kv_project_backward", "bda_set_tile_policy", "bda_last_error", "bda_version")
+           "bda_lowrank_linear", "bda_kv_project_backward", "bda_kv_project_plan", "bda_dense_project_plan", "bda_set_tile_policy", "bda_last_error", "bda_version")
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _lib = None
+
+
+KERNEL_NONE, KERNEL_GENERAL, KERNEL_MFMA, KERNEL_STREAM, KERNEL_LEAN, KERNEL_DECODE = 0, 1, 2, 3, 4, 5
+
+
+class LaunchPlan(ctypes.Structure):
+    """Mirror of bda_launch_plan."""
+    _fields_ = [(n, ctypes.c_int) for n in ("kernel", "tile_tokens", "tile_columns", "token_tiles", "column_tiles",
+                                            "workgroups", "threads", "lds_bytes", "rounds", "tile_by_tile",
+                                            "super_m", "super_n")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
 
 class BdaError(RuntimeError):
@@ -67,6 +80,11 @@ def load():
     lib.bda_kv_project_backward.restype = c_int
     lib.bda_kv_project_backward.argtypes = [vp, i64, vp, i64, vp, i64, i64, c_int, c_int, c_int, ip, ip,
                                             vp, i64, vp, i64, c_int, c_int, vp]
+    lib.bda_kv_project_plan.restype = c_int
+    lib.bda_kv_project_plan.argtypes = [i64, c_int, c_int, c_int, ip, ip, i64, i64, i64, c_int, c_int,
+                                        ctypes.POINTER(LaunchPlan)]
+    lib.bda_dense_project_plan.restype = c_int
+    lib.bda_dense_project_plan.argtypes = [i64, c_int, i64, i64, i64, i64, c_int, c_int, ctypes.POINTER(LaunchPlan)]
     lib.bda_set_tile_policy.restype = c_int
     lib.bda_set_tile_policy.argtypes = [c_int]
     lib.bda_last_error.restype = ctypes.c_char_p
@@ -209,3 +227,23 @@ def bda_kv_project_backward(c, ldc: int, d_out, ld_dout: int, C, ldC: int, T: in
                                        _int_array(H), _int_array(basis_offset), _ptr(grad_c), ld_gc,
                                        _ptr(grad_C), ld_gC, dtype,
                                        dtype if grad_dtype is None else grad_dtype, stream or None))
+
+
+def bda_kv_project_plan(T: int, d_c: int, d_h: int, H: Sequence[int], basis_offset: Sequence[int], dtype: int,
+                        out_dtype: Optional[int] = None, ldc: Optional[int] = None, ldC: Optional[int] = None,
+                        ld_out: Optional[int] = None) -> dict:
+    lib = load()
+    N = int(sum(H)) * d_h
+    plan = LaunchPlan()
+    _check(lib.bda_kv_project_plan(T, d_c, d_h, len(H), _int_array(H), _int_array(basis_offset), ldc or d_c, ldC or N,
+                                   ld_out or N, dtype, dtype if out_dtype is None else out_dtype, ctypes.byref(plan)))
+    return plan.as_dict()
+
+
+def bda_dense_project_plan(T: int, d_c: int, N: int, dtype: int, out_dtype: Optional[int] = None,
+                           ldc: Optional[int] = None, ldW: Optional[int] = None, ld_out: Optional[int] = None) -> dict:
+    lib = load()
+    plan = LaunchPlan()
+    _check(lib.bda_dense_project_plan(T, d_c, N, ldc or d_c, ldW or N, ld_out or N, dtype,
+                                      dtype if out_dtype is None else out_dtype, ctypes.byref(plan)))
+    return plan.as_dict()

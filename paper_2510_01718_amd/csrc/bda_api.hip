@@ -16,6 +16,17 @@ namespace {
 
 std::atomic<int> g_tile_policy{0};
 
+// Set by the *_plan entry points: the launchers then describe the launch instead of making it.
+thread_local bda_launch_plan* t_plan = nullptr;
+
+bool plan_only(const GemmArgs& a, int kernel, int bt, int bn, int workgroups, int threads, int lds, int rounds)
+{
+    if (!t_plan) return false;
+    *t_plan = bda_launch_plan{kernel, bt, bn, a.m_tiles, a.n_tiles, workgroups, threads, lds, rounds,
+                              a.lin_slots > 0 ? 1 : 0, a.sm, a.sn};
+    return true;
+}
+
 template <typename K>
 int set_max_lds(K kernel, int bytes, std::once_flag& flag)
 {
@@ -32,6 +43,10 @@ int launch_mfma(GemmArgs& a, hipStream_t st)
     static std::once_flag once;
     constexpr int lds = 2 * (64 * TT + 64 * TN) * kRowBytes;
     auto kern = gemm_mfma_kernel<X, OutT, TT, TN>;
+    {
+        const int64_t supers = (int64_t)((a.m_tiles + a.sm - 1) / a.sm) * ((a.n_tiles + a.sn - 1) / a.sn);
+        if (plan_only(a, BDA_KERNEL_MFMA, 64 * TT, 64 * TN, kNumXcd * a.sm * a.sn, 256, lds, (int)((supers + kNumXcd - 1) / kNumXcd))) return BDA_OK;
+    }
     if (int rc = set_max_lds(kern, lds, once)) return rc;
     hipLaunchKernelGGL(kern, dim3(kNumXcd * a.sm * a.sn), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
@@ -52,8 +67,6 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
     auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS, 0>;
     auto kern_plain = gemm_plain_kernel<X, OutT, 0, 4>;
     auto kern_half = gemm_plain_kernel<X, OutT, 0, 2>;
-    if (int rc = half_tokens ? set_max_lds(kern_half, lds_half, once_half)
-                 : plain ? set_max_lds(kern_plain, lds, once_plain) : set_max_lds(kern, lds, once)) return rc;
     a.n_super_m = (a.m_tiles + a.sm - 1) / a.sm;
     a.n_super_n = (a.n_tiles + a.sn - 1) / a.sn;
     a.dh_magic = a.d_h > 0 ? (((uint64_t)1 << 40) + a.d_h - 1) / a.d_h : 0;
@@ -87,6 +100,10 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
         a.xcd_count[x] = (int)std::min<int64_t>(per_die, total - first);
     }
     const int wgs_per_die = a.lin_slots ? a.lin_slots : a.sm * a.sn;
+    if (plan_only(a, plain || half_tokens ? BDA_KERNEL_LEAN : BDA_KERNEL_STREAM, half_tokens ? 128 : 256, 256,
+                  kNumXcd * wgs_per_die, 512, half_tokens ? lds_half : lds, a.rounds)) return BDA_OK;
+    if (int rc = half_tokens ? set_max_lds(kern_half, lds_half, once_half)
+                 : plain ? set_max_lds(kern_plain, lds, once_plain) : set_max_lds(kern, lds, once)) return rc;
     if (half_tokens) hipLaunchKernelGGL(kern_half, dim3(kNumXcd * wgs_per_die), dim3(512), lds_half, st, a);
     else if (plain) hipLaunchKernelGGL(kern_plain, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
     else hipLaunchKernelGGL(kern, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
@@ -99,9 +116,10 @@ int launch_decode(GemmArgs& a, hipStream_t st)
 {
     static std::once_flag once;
     auto kern = kv_decode_kernel<X, OutT>;
-    if (int rc = set_max_lds(kern, kDecodeMaxK * 64 + 32768, once)) return rc;
     const int lds = ((a.K + 15) / 16) * 1024 + 32768;
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
+    if (plan_only(a, BDA_KERNEL_DECODE, kDecodeMaxT, 32, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
+    if (int rc = set_max_lds(kern, kDecodeMaxK * 64 + 32768, once)) return rc;
     hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
@@ -110,6 +128,7 @@ int launch_decode(GemmArgs& a, hipStream_t st)
 template <typename InT, typename OutT>
 int launch_general(GemmArgs& a, int64_t N_total, hipStream_t st)
 {
+    if (plan_only(a, BDA_KERNEL_GENERAL, 64, 64, a.n_tiles * a.m_tiles, 256, 2 * 16 * 65 * 4, 1)) return BDA_OK;
     hipLaunchKernelGGL((gemm_general_kernel<InT, OutT>), dim3(a.n_tiles, a.m_tiles), dim3(256), 0, st, a, N_total);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
@@ -346,4 +365,37 @@ extern "C" int bda_lowrank_linear(const void* x, int64_t ldx, int64_t T, int d_i
         int64_t cols[1] = {nc};
         return run_gemm(a, 1, cols, dtype, dtype, (hipStream_t)stream);
     }
+}
+
+namespace {
+// Stand-ins for device pointers (16-byte aligned, far apart): the plan entry points run the same
+// validation and tile choice as the real calls and stop before any HIP call.
+void* const kFakeA = (void*)((uintptr_t)1 << 40);
+void* const kFakeB = (void*)((uintptr_t)2 << 40);
+void* const kFakeD = (void*)((uintptr_t)3 << 40);
+}  // namespace
+
+extern "C" int bda_kv_project_plan(int64_t T, int d_c, int d_h, int G, const int* H, const int* basis_offset,
+                                   int64_t ldc, int64_t ldC, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
+                                   bda_launch_plan* plan)
+{
+    clear_error();
+    if (!plan) return fail(BDA_EINVAL, "bda_kv_project_plan: NULL plan");
+    *plan = bda_launch_plan{BDA_KERNEL_NONE, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    t_plan = plan;
+    const int rc = bda_kv_project(kFakeA, ldc, T, d_c, d_h, G, H, basis_offset, kFakeB, ldC, kFakeD, ld_out, dtype, out_dtype, nullptr);
+    t_plan = nullptr;
+    return rc;
+}
+
+extern "C" int bda_dense_project_plan(int64_t T, int d_c, int64_t N, int64_t ldc, int64_t ldW, int64_t ld_out,
+                                      bda_dtype dtype, bda_dtype out_dtype, bda_launch_plan* plan)
+{
+    clear_error();
+    if (!plan) return fail(BDA_EINVAL, "bda_dense_project_plan: NULL plan");
+    *plan = bda_launch_plan{BDA_KERNEL_NONE, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    t_plan = plan;
+    const int rc = bda_dense_project(kFakeA, ldc, T, d_c, kFakeB, ldW, N, kFakeD, ld_out, dtype, out_dtype, nullptr);
+    t_plan = nullptr;
+    return rc;
 }

@@ -207,3 +207,72 @@ def test_workload_recipe_is_stable():
 
 def from64(x):
     return np.asarray(x, dtype=np.float64)
+
+
+# ------------------------------------------------------------------ launch-shape rules (host logic)
+def _plan(T, H, offs, dtype, d_c=512, d_h=128, **kw):
+    return bda.bda_kv_project_plan(T, d_c, d_h, H, offs, dtype, **kw)
+
+
+def test_launch_plan_benchmark_shapes():
+    """The tile choice and schedule of the configurations that are benchmarked (no GPU needed)."""
+    p = _plan(4096, [16, 16], [0, 0], bda.BDA_F16)                      # main workload: one 256 x 256 tile per CU
+    assert (p["kernel"], p["tile_tokens"], p["tile_columns"]) == (bda.KERNEL_LEAN, 256, 256)
+    assert (p["token_tiles"], p["column_tiles"], p["workgroups"], p["threads"]) == (16, 16, 256, 512)
+    assert (p["rounds"], p["tile_by_tile"], p["super_m"], p["super_n"]) == (1, 0, 4, 8)
+    assert p["lds_bytes"] == 160 * 1024
+    p = _plan(8192, [128, 128], [0, 0], bda.BDA_BF16)                   # V3 shape: 16 tiles per CU
+    assert (p["kernel"], p["tile_tokens"], p["rounds"], p["workgroups"]) == (bda.KERNEL_LEAN, 256, 16, 256)
+    for T in (1, 8, 32, 64):                                            # decode: one workgroup per 32 columns
+        p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
+        assert (p["kernel"], p["column_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 128, 128)
+    p = bda.bda_dense_project_plan(8192, 4096, 1024, bda.BDA_F16)       # BD linear, first GEMM
+    assert (p["kernel"], p["tile_tokens"], p["token_tiles"] * p["column_tiles"], p["rounds"]) == (bda.KERNEL_LEAN, 128, 256, 1)
+    p = _plan(64, [1], [0], bda.BDA_F32, d_c=64, d_h=32)                # config 1: float32
+    assert p["kernel"] == bda.KERNEL_GENERAL
+    assert _plan(0, [16, 16], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_NONE
+
+
+def test_launch_plan_tile_choice_by_rounds():
+    """128-token tiles where they need fewer than 1/0.56 times the rounds of 256-token tiles; dies
+    take single tiles where whole super-tiles would need more rounds."""
+    want = {100: (128, 1, 0), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
+            3072: (256, 1, 1), 4096: (256, 1, 0), 5120: (128, 3, 0), 8192: (256, 2, 0)}
+    for T, (tokens, rounds, by_tile) in want.items():
+        p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
+        assert p["kernel"] == bda.KERNEL_LEAN, T
+        assert (p["tile_tokens"], p["rounds"], p["tile_by_tile"]) == (tokens, rounds, by_tile), (T, p)
+        tiles = p["token_tiles"] * p["column_tiles"]
+        per_die = p["workgroups"] // 8
+        assert 8 * per_die * p["rounds"] >= tiles                      # every tile has a slot
+    p = _plan(1536, [16, 16], [0, 0], bda.BDA_F16)
+    assert (p["token_tiles"], p["column_tiles"], p["workgroups"]) == (12, 16, 192)   # 24 tiles per die, one round
+
+
+def test_launch_plan_preconditions_of_the_lean_kernel():
+    lean = bda.KERNEL_LEAN
+    assert _plan(4096, [16, 16], [208, 16], bda.BDA_F16)["kernel"] == lean        # windows off the 64 grid
+    assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, out_dtype=bda.BDA_F32)["kernel"] == lean
+    assert _plan(4096, [2, 4, 2], [0, 64, 384], bda.BDA_BF16)["kernel"] == lean   # three groups
+    # contraction not a multiple of 64 -> general streaming kernel (tile count >= 96), or register-staged
+    assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, d_c=520)["kernel"] == bda.KERNEL_STREAM
+    assert _plan(512, [16, 16], [0, 0], bda.BDA_F16, d_c=520)["kernel"] == bda.KERNEL_MFMA
+    # a group narrower than a 256-column tile
+    p = _plan(4096, [1], [0], bda.BDA_F16)
+    assert (p["kernel"], p["tile_tokens"], p["tile_columns"]) == (bda.KERNEL_MFMA, 128, 128)
+    # window start not a multiple of 8, row pitch not a multiple of 8, head width not a multiple of 32
+    assert _plan(4096, [16, 16], [4, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_GENERAL
+    assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, ldc=516)["kernel"] == bda.KERNEL_GENERAL
+    assert _plan(300, [4], [0], bda.BDA_F16, d_c=96, d_h=24)["kernel"] == bda.KERNEL_GENERAL
+    # the tile policy hook
+    try:
+        bda.bda_set_tile_policy(1)
+        assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_MFMA
+        bda.bda_set_tile_policy(3)
+        assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_STREAM
+        bda.bda_set_tile_policy(4)
+        assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16)["tile_tokens"] == 128
+    finally:
+        bda.bda_set_tile_policy(0)
+    with pytest.raises(bda.BdaError):
+        _plan(4096, [16, 16], [0, 400], bda.BDA_F16)                    # window outside the latent
