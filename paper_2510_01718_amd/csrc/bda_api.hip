@@ -202,13 +202,15 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         int64_t nt256 = 0;
         for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
         const int policy = g_tile_policy.load();
-        const int n_stage_id = a.ident ? (((a.d_h % 256) == 0 ? 256 : a.d_h) + kStreamSK - 1) / kStreamSK : 0;
+        const int id_width = (a.d_h % 256) == 0 ? 256 : a.d_h;          // window columns a 256-column tile needs
+        const int n_stage_id = a.ident ? (id_width + kStreamSK - 1) / kStreamSK : 0;
+        const int n_stage_id_lean = a.ident ? (id_width + 2 * kStreamSK - 1) / (2 * kStreamSK) : 0;   // double-width identity stages
         // Can the streaming kernels take this launch at all, and its lean variant (nothing in any
         // stage depends on the lane: see bda_gemm_plain.hpp)?
         bool stream_ok = (a.K + kStreamSK - 1) / kStreamSK + n_stage_id >= kStreamNS && a.d_h < (1 << 16);
         for (int g = 0; g < G; ++g) stream_ok = stream_ok && group_cols[g] < (1 << 24);   // exact x % d_h by multiplication
         bool plain = stream_ok && kStreamSK == 64 && kStreamNS == 2 && a.K % 64 == 0 && (!a.ident || a.d_h % 64 == 0)
-                     && a.K / 64 + n_stage_id >= 3 && a.K >= 64 && policy != 3 && policy != 1;
+                     && a.K / 64 + n_stage_id_lean >= 3 && a.K >= 64 && policy != 3 && policy != 1;
         for (int g = 0; g < G; ++g) plain = plain && group_cols[g] % 256 == 0;   // (window starts: multiples of 8, checked above)
         // Tile choice.  The lean kernel serves every tile count; its 128-token tile costs 0.53-0.56 of
         // its 256-token tile per round of tiles (measured), so the smaller tile is taken where it
@@ -226,7 +228,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
             choose_super(a, kSlotsPerXcd);
             // identity slice: stages of the streaming kernel (the slice of a 256-column tile is the
             // whole window, or the tile's own 256 columns of it when d_h is a multiple of 256)
-            a.n_stage_id = n_stage_id;
+            a.n_stage_id = plain ? n_stage_id_lean : n_stage_id;
         } else {
             build_tiles(a, G, group_cols, 128, 128);
             choose_super(a, 2 * kSlotsPerXcd);

@@ -179,7 +179,14 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     // Requests stage k of tile t into the slot at byte `slot_b`; loads j0 .. j0+3 (0: tokens, 4: weights).
     auto stage_soff_tok = [&](const StreamTile& t, int k) -> uint32_t {
         const int k0 = k * SK;
-        return k < nk ? (uint32_t)(k0 + (k0 >= t.a_off ? q.a_skip : 0)) * 2u : (uint32_t)(t.a_off + t.j_lo + (k - nk) * SK) * 2u;
+        return k < nk ? (uint32_t)(k0 + (k0 >= t.a_off ? q.a_skip : 0)) * 2u : (uint32_t)(t.a_off + t.j_lo + (k - nk) * (2 * SK)) * 2u;
+    };
+    // Identity stages are two stage lengths wide: window columns [j, j + 64) of the stage go to the
+    // token half of the slot and [j + 64, j + 128) to its weight half (same layout; an identity stage
+    // has no weights).  A wave's 64 output columns take their slice from one of the two: which one.
+    auto id_half = [&](const StreamTile& t, int k) -> int {
+        const int diff = t.rel_blk0 - (t.j_lo + (k - nk) * (2 * SK));
+        return (k >= nk && diff >= SK && diff < 2 * SK) ? 1 : 0;
     };
     // (a wave's token rows take PIT KiB of a slot's token half, its weight rows 4 KiB of the weight
     // half; `lds_b` is the slot plus 4 KiB per wave, so the token side steps back for PIT < 4)
@@ -206,9 +213,27 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         constexpr int j = decltype(jc)::value;
         if constexpr (j < PIT && !(DBG & 4)) lds_dma_imm<1024 * j>(t.rA, lds_b - tok_back, vt[j], soff);
     };
-    auto wgt_load = [&](auto jc, u32x4 rW, uint32_t lds_b, uint32_t soff) {
+    // The four loads of a stage that go to the weight half of the slot: rows of the weight tile, or
+    // (identity stage) the second 64 window columns of the token rows.  Uniform choice per stage.
+    // (With 128-token tiles the second token set has two loads per wave; the other two keep the
+    // stage's load count and write zeros to the unused part of the weight half, 2 KiB per wave.)
+    auto slot_of = [&](uint32_t lds_b) { return lds_b - (uint32_t)wave * 4096u; };   // slot start (absolute LDS address)
+    struct Second { u32x4 r; uint32_t base, base_unused; uint32_t so, so_step; uint32_t v[4]; };
+    auto second_set = [&](const StreamTile& t, int k, uint32_t lds_b, uint32_t ts, const uint32_t (&vt)[PIT]) -> Second {
+        Second z;
+        const bool id = k >= nk;
+        z.r = id ? t.rA : t.rB;
+        z.base = id ? lds_b - tok_back : lds_b;
+        z.base_unused = id ? slot_of(lds_b) + (uint32_t)(7 * PIT * 1024) + (uint32_t)wave * (uint32_t)((4 - PIT) * 1024) : lds_b;
+        z.so = id ? ts + (uint32_t)(2 * SK) : (uint32_t)(k * SK) * wgt_row_bytes;
+        z.so_step = id ? 0u : wgt_step;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) z.v[j] = id ? (j < PIT ? vt[j < PIT ? j : 0] : kBadOffset) : vo_wgt[j & 1];
+        return z;
+    };
+    auto wgt_load = [&](auto jc, const Second& z) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (!(DBG & 4)) lds_dma_imm<TOK_BYTES + 1024 * j>(rW, lds_b, vo_wgt[j & 1], soff);
+        if constexpr (!(DBG & 4)) lds_dma_imm<TOK_BYTES + 1024 * j>(z.r, j < PIT ? z.base : z.base_unused, z.v[j], z.so + (uint32_t)j * z.so_step);
     };
     auto produce_all = [&](const StreamTile& t, int k, uint32_t slot_b) {
         const uint32_t lds_b = slot_b + wave_lds;
@@ -219,13 +244,11 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         tok_load(std::integral_constant<int, 1>{}, t, lds_b, ts, vt);
         tok_load(std::integral_constant<int, 2>{}, t, lds_b, ts, vt);
         tok_load(std::integral_constant<int, 3>{}, t, lds_b, ts, vt);
-        u32x4 rW = t.rB;
-        if (k >= nk) rW[2] = 0;
-        const uint32_t ws = k < nk ? (uint32_t)(k * SK) * wgt_row_bytes : 0u;
-        wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws);
-        wgt_load(std::integral_constant<int, 1>{}, rW, lds_b, ws + wgt_step);
-        wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step);
-        wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step);
+        const Second z = second_set(t, k, lds_b, ts, vt);
+        wgt_load(std::integral_constant<int, 0>{}, z);
+        wgt_load(std::integral_constant<int, 1>{}, z);
+        wgt_load(std::integral_constant<int, 2>{}, z);
+        wgt_load(std::integral_constant<int, 3>{}, z);
     };
 
     // ---- consumer ---------------------------------------------------------------------------------
@@ -276,8 +299,8 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             fw[ni] = (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
         }
     };
-    auto read_t = [&](int ks, u32x4 (&ft)[TT]) {
-        const uint32_t a = a_tok ^ (uint32_t)(ks << 5);
+    auto read_t = [&](int ks, u32x4 (&ft)[TT], uint32_t half_off = 0u) {   // half_off: TOK_BYTES for the weight half (identity stages)
+        const uint32_t a = (a_tok ^ (uint32_t)(ks << 5)) + half_off;
 #pragma unroll
         for (int ti = 0; ti < TT; ++ti) ft[ti] = *(lds_u32x4)(uintptr_t)(a + ti * (32 * RB));
     };
@@ -308,7 +331,10 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         constexpr bool REG = decltype(regular)::value;
         constexpr bool FIRST = decltype(first_of_tile)::value;   // only then may result stores be in flight
         const bool next_regular = kc + 1 < nk || kc + 1 == S;
-        const int jc = cur.j_lo + (kc - nk) * SK;
+        const int half_cur = REG ? 0 : id_half(cur, kc);
+        const uint32_t off_cur = half_cur ? (uint32_t)TOK_BYTES : 0u;
+        const uint32_t off_next = (!next_regular && id_half(cur, kc + 1)) ? (uint32_t)TOK_BYTES : 0u;
+        const int jc = cur.j_lo + (kc - nk) * (2 * SK) + half_cur * SK;
         u32x4 idf[2];
         if constexpr (!REG) make_idf(idf);
         BDA_STAMP(1);
@@ -316,14 +342,14 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         // runs ahead to the barrier and leaves the other to work through the stage alone.  Alternating
         // the priority by half stages keeps them side by side (measured: 4-8 % faster).
         if (wt == 0) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-        if constexpr (REG) { read_w(1, fw1); read_t(1, ft1); } else read_t(1, ft1);
+        if constexpr (REG) { read_w(1, fw1); read_t(1, ft1); } else read_t(1, ft1, off_cur);
         if constexpr (REG) {
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
                 for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw0[ni], ft0[ti], acc[ni][ti]);
         } else mma_identity(idf, jc, ft0);
-        if constexpr (REG) { read_w(2, fw0); read_t(2, ft0); } else read_t(2, ft0);
+        if constexpr (REG) { read_w(2, fw0); read_t(2, ft0); } else read_t(2, ft0, off_cur);
         if constexpr (REG) {
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni)
@@ -331,16 +357,14 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
                 for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw1[ni], ft1[ti], acc[ni][ti]);
         } else mma_identity(idf, jc + 16, ft1);
         // last read of this slot
-        if constexpr (REG) { read_w(3, fw1); read_t(3, ft1); } else read_t(3, ft1);
+        if constexpr (REG) { read_w(3, fw1); read_t(3, ft1); } else read_t(3, ft1, off_cur);
         flip_slot();
         // uniform part of the requests that follow the barrier
         const uint32_t lds_b = slot_b + wave_lds;
         const uint32_t ts = stage_soff_tok(pt, pk);
         uint32_t vt[PIT];
         tok_voffs(pt, pk, vt);
-        u32x4 rW = pt.rB;
-        if (pk >= nk) rW[2] = 0;              // identity stage: the weight half of the slot is filled with zeros
-        const uint32_t ws = pk < nk ? (uint32_t)(pk * SK) * wgt_row_bytes : 0u;
+        const Second z = second_set(pt, pk, lds_b, ts, vt);
         BDA_STAMP(2);
         if (FIRST && relaxed) wait_vmcnt<STORES>(); else wait_vmcnt<0>();
         BDA_STAMP(3);
@@ -371,31 +395,31 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         BDA_STAMP(5);
         // first fragments of the next stage, out of the other slot
         if (next_regular) read_w(0, fw0);
-        read_t(0, ft0);
+        read_t(0, ft0, off_next);
         if constexpr (REG && TT == 4) {
             acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]); acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[0][2] = mm(fw1[0], ft1[2], acc[0][2]); acc[0][3] = mm(fw1[0], ft1[3], acc[0][3]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 1>{}, rW, lds_b, ws + wgt_step); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 1>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mm(fw1[1], ft1[0], acc[1][0]); acc[1][1] = mm(fw1[1], ft1[1], acc[1][1]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw1[1], ft1[2], acc[1][2]); acc[1][3] = mm(fw1[1], ft1[3], acc[1][3]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
         } else if constexpr (REG) {
             acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 1>{}, rW, lds_b, ws + wgt_step); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 1>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mm(fw1[1], ft1[0], acc[1][0]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][1] = mm(fw1[1], ft1[1], acc[1][1]);
-            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step); __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
         } else {
             mma_identity(idf, jc + 48, ft1);
-            wgt_load(std::integral_constant<int, 0>{}, rW, lds_b, ws);
-            wgt_load(std::integral_constant<int, 1>{}, rW, lds_b, ws + wgt_step);
-            wgt_load(std::integral_constant<int, 2>{}, rW, lds_b, ws + 2 * wgt_step);
-            wgt_load(std::integral_constant<int, 3>{}, rW, lds_b, ws + 3 * wgt_step);
+            wgt_load(std::integral_constant<int, 0>{}, z);
+            wgt_load(std::integral_constant<int, 1>{}, z);
+            wgt_load(std::integral_constant<int, 2>{}, z);
+            wgt_load(std::integral_constant<int, 3>{}, z);
         }
         slot_b = (uint32_t)STAGE_BYTES - slot_b;
     };

@@ -109,6 +109,19 @@ def test_kv_lean_tile_by_tile_order_two_rounds():
     _run_kv_case(w, [0, 384], policy=4)
 
 
+@pytest.mark.parametrize("policy", [2, 3, 4])
+@pytest.mark.parametrize("d_c,d_h,H,offs", [(256, 64, [8, 4], [0, 192]),        # window narrower than an identity stage
+                                            (448, 192, [4], [64]),              # one and a half identity stages
+                                            (512, 256, [2, 1], [256, 0]),       # window = tile width: two stages
+                                            (1024, 512, [1, 1], [512, 128])])   # tile takes its own 256 columns of the window
+def test_kv_lean_head_widths(policy, d_c, d_h, H, offs):
+    """Head widths other than 128 through the streaming kernels: the identity slice of a tile is
+    64 ... 256 window columns, taken in stages of 128 (lean) or 64 (general)."""
+    w = wl.custom_kv_workload("widths", T=300, d_c=d_c, d_h=d_h, H=H, std=0.02, rms_norm=True,
+                              dtype=wl.F16, seed=31)
+    _run_kv_case(w, offs, policy=policy)
+
+
 @pytest.mark.parametrize("T", [100, 1300, 1536])
 def test_kv_lean_automatic_tile_choice(T):
     """Automatic policy on the V2-Lite shape at token counts that select 128-token tiles
