@@ -282,6 +282,22 @@ def main() -> int:
                                      "gbs": b4 / t4 / 1e9, "frac_hbm": b4 / t4 / 1e9 / HBM_PEAK_GBS,
                                      "tokens_per_s": T4 / t4}
         log(f"v3: {t4 * 1e6:.1f} us, {f4 / t4 / 1e12:.0f} TFLOP/s, {b4 / t4 / 1e9:.0f} GB/s")
+        # decode shapes at the V3 width (not a BASELINE config; 24 MiB of C per launch, 12 rotating
+        # copies so that each launch streams them from HBM): the one small-T case with enough bytes
+        # for the HBM rate to show
+        n_w4 = 12
+        C4_rot = C4.unsqueeze(0).repeat(n_w4, 1, 1).contiguous()
+        dec4 = {}
+        for Td in (1, 8, 32, 64):
+            cd = c4[:Td].contiguous()
+            od = torch.empty((Td, N4), dtype=torch.int16, device="cuda")
+            t_d = bench_small(lambda i, s: bda.bda_kv_project(cd, d_c, Td, d_c, d_h, [128, 128], [0, 0], C4_rot[i % n_w4], N4,
+                                                              od, N4, wl.BF16, wl.BF16, s), max(8, min(240, args.steps)), max(2, min(48, args.warmup)))
+            by = (Td * d_c + K * N4 + Td * N4) * 2.0
+            dec4[f"T{Td}"] = {"us": t_d * 1e6, "gbs": by / t_d / 1e9, "frac_hbm": by / t_d / 1e9 / HBM_PEAK_GBS}
+            log(f"decode at V3 width T={Td}: {t_d * 1e6:.2f} us, {by / t_d / 1e9:.0f} GB/s")
+        extra["decode_v3_width"] = dec4
+        del C4_rot
         W4 = dev(wl.to_storage(rng.standard_normal((d_c, N4)) * 0.02, wl.BF16)[0], wl.BF16)
         t4d = bench_small(lambda i, s: bda.bda_dense_project(c4, d_c, T4, d_c, W4, N4, N4, o4[i % 2], N4,
                                                              wl.BF16, wl.BF16, s), max(3, args.steps // 10), max(1, args.warmup // 10))

@@ -111,18 +111,47 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
 
-template <typename X, typename OutT>
-int launch_decode(GemmArgs& a, hipStream_t st)
+template <typename X, typename OutT, int NTB>
+int launch_decode_blocks(GemmArgs& a, hipStream_t st)
 {
     static std::once_flag once;
-    auto kern = kv_decode_kernel<X, OutT>;
-    const int lds = ((a.K + 15) / 16) * 1024 + 32768;
+    auto kern = kv_decode_kernel<X, OutT, NTB>;
+    const int part = NTB * 16384;                           // float32 partial sums of the four waves
+    const int lds = ((a.K + 15) / 16) * 1024 + part;
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
-    if (plan_only(a, BDA_KERNEL_DECODE, kDecodeMaxT, 32, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
-    if (int rc = set_max_lds(kern, kDecodeMaxK * 64 + 32768, once)) return rc;
+    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, 32, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
+    if (int rc = set_max_lds(kern, kDecodeMaxK * 64 + part, once)) return rc;
     hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
+template <typename X, typename OutT, int NTB>
+int launch_decode_wide_blocks(GemmArgs& a, hipStream_t st)
+{
+    static std::once_flag once;
+    auto kern = kv_decode_wide_kernel<X, OutT, NTB>;
+    const int nks = (a.K + 15) / 16;
+    const int lds = ((nks + 1) & ~1) * 4096 + ((a.K + 63) / 64) * NTB * 4096;   // slice of C, token rows
+    const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
+    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, kDecodeWideCols, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
+    if (int rc = set_max_lds(kern, kDecodeWideMaxKS * 4096 + (kDecodeWideMaxKS / 4) * NTB * 4096, once)) return rc;
+    hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
+template <typename X, typename OutT>
+int launch_decode_wide(GemmArgs& a, hipStream_t st)
+{
+    return a.M <= 32 ? launch_decode_wide_blocks<X, OutT, 1>(a, st) : launch_decode_wide_blocks<X, OutT, 2>(a, st);
+}
+
+// Two blocks of 32 token rows per workgroup up to 64 tokens, four up to 128.
+template <typename X, typename OutT>
+int launch_decode(GemmArgs& a, hipStream_t st)
+{
+    return a.M <= 64 ? launch_decode_blocks<X, OutT, 2>(a, st) : launch_decode_blocks<X, OutT, 4>(a, st);
 }
 
 template <typename InT, typename OutT>
@@ -188,7 +217,31 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     fast = fast && a.lda < max_ld && a.ldd < max_ld && a.ldb < max_ld && (int64_t)a.K * a.ldb * 2 < ((int64_t)1 << 31);
     for (int g = 0; g < G; ++g) fast = fast && a.a_off[g] % 8 == 0 && group_cols[g] % 8 == 0;
 
-    if (fast && ident_vec && g_tile_policy.load() == 0 && a.M <= kDecodeMaxT && a.K <= kDecodeMaxK) {
+    // Small-T kernels (policy 5 forces the wide-slice one wherever it applies and otherwise acts as 0).
+    // Measured on cold weights, K = 384: with 32-column slices the time grows with the number of
+    // workgroups per compute unit, so beyond about 20 k columns one workgroup per 128 columns wins
+    // (N = 32768: 9.5-12 us against 12.5-17 us), below it loses to the finer split (N = 4096:
+    // 6.7-8.6 against 5.3-6.0); for 65 .. 128 tokens the 32-column kernel with four token blocks
+    // beats 128-token tiles while every slice has a compute unit of its own (N = 4096: 6.6-8.0 us
+    // against 10.6) and loses beyond.
+    const int policy0 = g_tile_policy.load();
+    const bool small_policy = policy0 == 0 || policy0 == 5;
+    int64_t n_slices128 = 0, n_slices32 = 0;
+    for (int g = 0; g < G; ++g) {
+        n_slices128 += (group_cols[g] + kDecodeWideCols - 1) / kDecodeWideCols;
+        n_slices32 += (group_cols[g] + 31) / 32;
+    }
+    if (fast && ident_vec && a.M <= kDecodeWideMaxT && a.K <= 16 * kDecodeWideMaxKS
+        && (policy0 == 5 || (policy0 == 0 && n_slices128 >= 160))) {
+        // a few tokens, wide output: stream the weights once, 128 output columns per workgroup
+        build_tiles(a, G, group_cols, kDecodeWideMaxT, kDecodeWideCols);
+        a.sm = a.sn = 1;
+        if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_decode_wide<F16, uint16_t>(a, st);
+        if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_decode_wide<F16, float>(a, st);
+        if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_decode_wide<BF16, uint16_t>(a, st);
+        if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_decode_wide<BF16, float>(a, st);
+    }
+    if (fast && ident_vec && small_policy && a.M <= kDecodeMaxT && a.K <= kDecodeMaxK && (a.M <= 64 || n_slices32 <= 256)) {
         // a few tokens: stream the weights once, 32 output columns per workgroup
         build_tiles(a, G, group_cols, kDecodeMaxT, 32);
         a.sm = a.sn = 1;
@@ -201,7 +254,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         const int64_t mt256 = (a.M + 255) / 256, mt128 = (a.M + 127) / 128;
         int64_t nt256 = 0;
         for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
-        const int policy = g_tile_policy.load();
+        const int policy = policy0 == 5 ? 0 : policy0;
         const int id_width = (a.d_h % 256) == 0 ? 256 : a.d_h;          // window columns a 256-column tile needs
         const int n_stage_id = a.ident ? (id_width + kStreamSK - 1) / kStreamSK : 0;
         const int n_stage_id_lean = a.ident ? (id_width + 2 * kStreamSK - 1) / (2 * kStreamSK) : 0;   // double-width identity stages
@@ -271,7 +324,7 @@ using namespace bda;
 extern "C" int bda_set_tile_policy(int policy)
 {
     clear_error();
-    if (policy < 0 || policy > 4) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0 .. 4");
+    if (policy < 0 || policy > 5) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0 .. 5");
     return g_tile_policy.exchange(policy);
 }
 

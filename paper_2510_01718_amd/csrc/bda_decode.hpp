@@ -1,7 +1,8 @@
-// Small-T ("decode") kernel of libbda for gfx950: T <= 64 tokens.
+// Small-T ("decode") kernel of libbda for gfx950: T <= 128 tokens (NTB blocks of 32 token rows per
+// workgroup: 2 for T <= 64, 4 above).
 //
 // With a handful of tokens the projection is a stream over the weights: every element of C is read
-// exactly once and used for at most 64 multiply-adds, so the kernel is organised around that read
+// exactly once and used for at most 128 multiply-adds, so the kernel is organised around that read
 // (bandwidth / latency bound), not around MFMA occupancy:
 //   * one workgroup per 32-column slice of the output, all K rows of it: its part of C
 //     (K x 64 bytes) goes global -> LDS in one burst of LDS DMA loads issued at kernel start;
@@ -16,10 +17,10 @@
 
 namespace bda {
 
-constexpr int kDecodeMaxT = 64;
+constexpr int kDecodeMaxT = 128;
 constexpr int kDecodeMaxK = 1536;       // K x 64 bytes of LDS for the slice of C
 
-template <typename X, typename OutT>
+template <typename X, typename OutT, int NTB>
 __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -58,11 +59,11 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
     }
 
     // ---- token fragments for this wave's k-steps (ks = wave, wave + 4, ...) --------------------------
-    const int n_tb = T > 32 ? 2 : 1;
+    const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
     const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
-    f32x16 acc[2];
+    f32x16 acc[NTB];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[tb][r] = 0.0f;
 
@@ -75,21 +76,21 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
 
     // first the token loads of all this wave's k-steps (they overlap the DMA), in chunks of 6 k-steps
     for (int ks0 = wave; ks0 < nks; ks0 += 4 * 6) {
-        u32x4 ft[6][2];
+        u32x4 ft[6][NTB];
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
             const int ks = ks0 + 4 * i;
             const int k = ks * 16 + 8 * lhi;
             const int col = k < a_off ? k : k + p.a_skip;
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
+            for (int tb = 0; tb < NTB; ++tb) {
                 const bool ok = ks < nks && k < p.K && tb < n_tb;
                 ft[i][tb] = __builtin_amdgcn_raw_buffer_load_b128(
                     rA, ok ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset, 0, 0);
             }
         }
         if (ks0 == wave) {                                // the slice of C must have landed (all waves)
-            wait_vmcnt<12>();                             // the 12 token loads above may still fly
+            wait_vmcnt<6 * NTB>();                        // the token loads above may still fly
             __syncthreads();
         }
 #pragma unroll
@@ -100,8 +101,9 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024 + 256));
                 const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
                 const u32x4 fw = {lo2[0], lo2[1], hi2[0], hi2[1]};
-                acc[0] = X::mfma(fw, ft[i][0], acc[0]);
-                if (n_tb > 1) acc[1] = X::mfma(fw, ft[i][1], acc[1]);
+#pragma unroll
+                for (int tb = 0; tb < NTB; ++tb)           // (blocks past T hold zeros)
+                    acc[tb] = X::mfma(fw, ft[i][tb], acc[tb]);
             }
         }
     }
@@ -113,24 +115,24 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
     // ---- fixed-order reduction over the four waves ------------------------------------------------
     float* part = (float*)(smem + wgt_bytes);            // [wave][tb][r][lane]
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int tb = 0; tb < NTB; ++tb)
         if (tb < n_tb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) part[((wave * 2 + tb) * 16 + r) * 64 + lane] = acc[tb][r];
+            for (int r = 0; r < 16; ++r) part[((wave * NTB + tb) * 16 + r) * 64 + lane] = acc[tb][r];
     __syncthreads();
     // wave w finishes accumulator rows 4 w .. 4 w + 3 = output columns 8 w + 4 lhi + 0..3
     const int col = 8 * wave + 4 * lhi;
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
                                                 ((int64_t)(T - 1) * p.ldd + cols_left) * (int64_t)sizeof(OutT));
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
+    for (int tb = 0; tb < NTB; ++tb) {
         if (tb >= n_tb) break;
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             float s = 0.0f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) s += part[((w * 2 + tb) * 16 + 4 * wave + e) * 64 + lane];
+            for (int w = 0; w < 4; ++w) s += part[((w * NTB + tb) * 16 + 4 * wave + e) * 64 + lane];
             v[e] = s;
         }
         const int t = tb * 32 + l31;
@@ -152,6 +154,164 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
             o[0] = X::pack2(v[0], v[1]);
             o[1] = X::pack2(v[2], v[3]);
             __builtin_amdgcn_raw_buffer_store_b64(o, rD, off, 0, 0);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Wide-slice variant for T <= 64 and K <= 384: one workgroup per 128-column slice of the output.
+//
+// The 32-column kernel above needs N / 32 workgroups, which for a wide projection is several per
+// compute unit one after the other, each with its own burst, reduction and tail.  Here a workgroup
+// takes 128 columns (K x 256 bytes of C, up to 96 KiB in flight per compute unit from the first
+// instruction on), each of its four waves owns 32 of them for the whole of K, so there is no
+// reduction between waves, and the MFMAs of a quarter of the k-steps start as soon as that quarter
+// of the slice has landed.
+//   * C slice in LDS: [k][256 bytes]; the 16-byte pieces of row k sit at position piece ^ 4 (k & 3),
+//     so that the transposing reads of a wave (rows k .. k + 3, its own 64 bytes) hit 16 different
+//     pieces per 32 lanes;
+//   * the token rows go through LDS too (full 128-byte pieces per row and request, issued before the
+//     requests for C: they hit L2, and the in-order counter then covers them with the first chunk);
+//   * the identity slice is added in float32 from the latent, as above.
+constexpr int kDecodeWideMaxT = 64;
+constexpr int kDecodeWideMaxKS = 24;    // k-steps of 16: K <= 384
+constexpr int kDecodeWideCols = 128;
+
+template <typename X, typename OutT, int NTB>
+__global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    constexpr int CH = 6;                                 // k-steps per chunk (four chunks)
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, lhi = lane >> 5;
+
+    const int per_xcd = (p.n_tiles + kNumXcd - 1) / kNumXcd;
+    const int slice = (int)(blockIdx.x % kNumXcd) * per_xcd + (int)(blockIdx.x / kNumXcd);
+    if (slice >= p.n_tiles) return;
+    int g = 0;
+    while (g + 1 < p.n_groups && slice >= p.tile_start[g + 1]) ++g;
+    const int rel0 = (slice - p.tile_start[g]) * kDecodeWideCols;
+    const int64_t n0 = p.col_start[g] + rel0;
+    const int64_t left = p.col_start[g + 1] - n0;
+    const int cols_left = (int)(left > kDecodeWideCols ? kDecodeWideCols : left);
+    const int a_off = p.a_off[g];
+    const int T = (int)p.M;
+    const int nks = (p.K + 15) >> 4;                     // <= kDecodeWideMaxKS (host contract)
+    const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
+
+    // ---- the token rows: [64-k stage][token][128 bytes] behind the slice of C, piece q of a row at
+    // position q ^ tok_swz<64>(row); one request = 8 rows x 128 bytes, the waves take turns -----------
+    const int issued = (nks + 1) & ~1;                   // requests per wave for C: one per k-step, a filler for an odd count
+    const int n_st = (p.K + 63) >> 6;
+    const uint32_t tok_lds = (uint32_t)issued * 4096u;
+    const u32x4 rA = make_rsrc_words(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    {
+        const int row8 = lane >> 3;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + tok_lds;
+        const int n_req = n_st * NTB * 4;
+        for (int i = wave; i < n_req; i += 4) {           // request i: stage i / (4 NTB), rows 8 (i % (4 NTB)) .. + 7
+            const int st = i / (4 * NTB), row = 8 * (i % (4 * NTB)) + row8;
+            const int k = 64 * st + 8 * ((lane & 7) ^ tok_swz<64>(row & 15));
+            const int col = k < a_off ? k : k + p.a_skip;
+            lds_dma1(rA, lds0 + (uint32_t)i * 1024u,
+                     row < T && k < p.K ? (uint32_t)row * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset);
+        }
+    }
+
+    // ---- the slice of C: wave w requests rows 16 ks + 4 w .. + 3 of every k-step, in k order -------
+    const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
+    {
+        const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
+        const int r = lane >> 4;                                      // row within the instruction = row & 3
+        const int piece = (lane & 15) ^ (4 * r);                      // global piece held at LDS position lane & 15
+        const uint32_t lane_off = piece * 8 < cols_left ? (uint32_t)(4 * wave + r) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u;
+#pragma unroll
+        for (int ks = 0; ks < kDecodeWideMaxKS; ks += 2) {            // rows past K fall outside rB's range -> zeros
+            if (ks < nks) {
+                const uint32_t v0 = lane_off + (uint32_t)(ks * 16) * row_bytes;
+                const uint32_t v1 = ks + 1 < nks ? lane_off + (uint32_t)((ks + 1) * 16) * row_bytes : kBadOffset;
+                lds_dma1(rB, lds0 + (uint32_t)ks * 4096u, v0);
+                lds_dma1(rB, lds0 + (uint32_t)(ks + 1) * 4096u, v1);
+            }
+        }
+    }
+
+    f32x16 acc[NTB];
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[tb][r] = 0.0f;
+
+    // transposing-read address: 16-lane group gq, s = lane % 16: row 8 lhi + s / 4 (+ 4 for the second
+    // read), columns 32 wave + 16 (gq & 1) + 4 (s & 3) .. + 3
+    const int c_s = lane & 15, c_gq = lane >> 4;
+    const int w_col = 32 * wave + 16 * (c_gq & 1) + 4 * (c_s & 3);
+    const uint32_t w_rd = (uint32_t)((8 * lhi + (c_s >> 2)) * 256 + (((w_col >> 3) ^ (4 * (c_s >> 2))) << 4) + ((w_col & 4) << 1));
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+
+    // fragment read of token block tb, k-step ks: row 32 tb + l31, pieces 2 (ks & 3) + lhi of stage ks / 4
+    typedef __attribute__((address_space(3))) const u32x4* lds_u32x4;
+    const uint32_t t_rd = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + tok_lds
+                          + (uint32_t)(l31 * 128 + ((lhi ^ tok_swz<64>(l31 & 15)) << 4));
+
+    // ---- four chunks of six k-steps: wait for this wave's requests of the chunk, meet the others ---
+    // (the token requests were issued first, so they are complete whenever a request for C is)
+#pragma unroll
+    for (int c = 0; c < kDecodeWideMaxKS / CH; ++c) {
+        const int rem = issued - CH * (c + 1);            // requests of later chunks may still fly
+        if (rem >= 18) wait_vmcnt<18>();
+        else if (rem >= 12) wait_vmcnt<12>();
+        else if (rem >= 6) wait_vmcnt<6>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        const int ks_end = nks < CH * (c + 1) ? nks : CH * (c + 1);
+        for (int ks = CH * c; ks < ks_end; ++ks) {       // (a plain loop: the accumulators stay where they are)
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 4096));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 4096 + 1024));
+            const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+            const u32x4 fw = {lo2[0], lo2[1], hi2[0], hi2[1]};
+            const uint32_t ta = (t_rd + (uint32_t)((ks >> 2) * (NTB * 4096))) ^ (uint32_t)((ks & 3) << 5);
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb)               // (blocks past T hold zeros)
+                acc[tb] = X::mfma(fw, *(lds_u32x4)(uintptr_t)(ta + tb * 4096), acc[tb]);
+        }
+    }
+
+    // ---- epilogue: lane (token l31, half lhi) holds columns 32 wave + 8 q + 4 lhi + 0..3, q = 0..3 ---
+    const __amdgpu_buffer_rsrc_t rI = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
+                                                ((int64_t)(T - 1) * p.ldd + cols_left) * (int64_t)sizeof(OutT));
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb) {
+        if (tb >= n_tb) break;
+        const int t = tb * 32 + l31;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = 32 * wave + 8 * q + 4 * lhi;
+            float v[4] = {acc[tb][4 * q], acc[tb][4 * q + 1], acc[tb][4 * q + 2], acc[tb][4 * q + 3]};
+            if (p.ident) {
+                const int j = (rel0 + col) % p.d_h;
+                const u32x2 idv = __builtin_amdgcn_raw_buffer_load_b64(
+                    rI, col < cols_left ? (uint32_t)t * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+                v[0] += X::to_f32((uint16_t)(idv[0] & 0xffffu));
+                v[1] += X::to_f32((uint16_t)(idv[0] >> 16));
+                v[2] += X::to_f32((uint16_t)(idv[1] & 0xffffu));
+                v[3] += X::to_f32((uint16_t)(idv[1] >> 16));
+            }
+            const uint32_t off = col < cols_left ? (uint32_t)t * (uint32_t)(p.ldd * sizeof(OutT)) + (uint32_t)col * (uint32_t)sizeof(OutT) : kBadOffset;
+            if constexpr (sizeof(OutT) == 4) {
+                const f32x4 vf = {v[0], v[1], v[2], v[3]};
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, off, 0, 0);
+            } else {
+                u32x2 o;
+                o[0] = X::pack2(v[0], v[1]);
+                o[1] = X::pack2(v[2], v[3]);
+                __builtin_amdgcn_raw_buffer_store_b64(o, rD, off, 0, 0);
+            }
         }
     }
 }

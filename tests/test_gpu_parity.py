@@ -49,13 +49,32 @@ def test_config1_tiny_fp32():
     assert rel < 1e-5
 
 
-@pytest.mark.parametrize("T", [1, 8, 32, 64])
+@pytest.mark.parametrize("T", [1, 8, 32, 64, 65, 128])
 def test_config3_decode_shapes(T):
     w = wl.kv_workload("decode", T=T)
     _run_kv_case(w, [0, 0])
 
 
-@pytest.mark.parametrize("T", [1, 7, 33, 64])
+@pytest.mark.parametrize("T", [1, 8, 32, 33, 64])
+def test_config3_decode_shapes_wide_slices(T):
+    # policy 5: the 128-column small-T kernel, which the library picks by itself only for outputs
+    # wider than about 20 k columns
+    w = wl.kv_workload("decode", T=T)
+    _run_kv_case(w, [0, 0], policy=5)
+
+
+@pytest.mark.parametrize("T", [1, 31, 64])
+@pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, wl.F32)])
+def test_decode_wide_slices_automatic(T, dtype, out_dtype):
+    # 160 slices of 128 columns (two groups, different windows off the 64 grid): the width from which
+    # the wide-slice kernel is the automatic choice
+    w = wl.custom_kv_workload("dec_wide", T=T, d_c=512, d_h=128, H=[100, 60], std=0.02, rms_norm=True, dtype=dtype, seed=50 + T)
+    p = bda.bda_kv_project_plan(T, 512, 128, [100, 60], [72, 384], dtype, out_dtype=out_dtype)
+    assert (p["kernel"], p["tile_columns"], p["workgroups"]) == (bda.KERNEL_DECODE, 128, 160)
+    _run_kv_case(w, [72, 384], out_dtype=out_dtype)
+
+
+@pytest.mark.parametrize("T", [1, 7, 33, 64, 65, 97, 128])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.BF16, wl.F32)])
 def test_decode_kernel_groups_and_offsets(T, dtype, out_dtype):
     # the small-T kernel: two groups with different windows, a group that ends inside a 32-column
@@ -66,6 +85,15 @@ def test_decode_kernel_groups_and_offsets(T, dtype, out_dtype):
     _run_kv_case(w, [56, 0], out_dtype=out_dtype)
     w = wl.custom_kv_workload("dec_c", T=T, d_c=1152, d_h=64, H=[5], std=0.02, rms_norm=True, dtype=dtype, seed=42 + T)
     _run_kv_case(w, [512], out_dtype=out_dtype)
+    if T <= 64:                                          # the same through the 128-column kernel (dec_c: K > 384, falls back)
+        w = wl.custom_kv_workload("dec_a", T=T, d_c=512, d_h=128, H=[3, 2], std=0.02, rms_norm=True, dtype=dtype, seed=40 + T)
+        _run_kv_case(w, [64, 384], out_dtype=out_dtype, policy=5)
+        w = wl.custom_kv_workload("dec_b", T=T, d_c=96, d_h=40, H=[1, 2], std=0.1, rms_norm=True, dtype=dtype, seed=41 + T)
+        _run_kv_case(w, [56, 0], out_dtype=out_dtype, policy=5)
+        w = wl.custom_kv_workload("dec_c", T=T, d_c=1152, d_h=64, H=[5], std=0.02, rms_norm=True, dtype=dtype, seed=42 + T)
+        _run_kv_case(w, [512], out_dtype=out_dtype, policy=5)
+        w = wl.custom_kv_workload("dec_d", T=T, d_c=440, d_h=56, H=[5, 1], std=0.05, rms_norm=True, dtype=dtype, seed=43 + T)
+        _run_kv_case(w, [0, 384], out_dtype=out_dtype, policy=5)   # K = 384 at the limit, ragged last slices (280 and 56 columns)
 
 
 @pytest.mark.parametrize("policy", [1, 2])

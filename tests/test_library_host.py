@@ -226,6 +226,16 @@ def test_launch_plan_benchmark_shapes():
     for T in (1, 8, 32, 64):                                            # decode: one workgroup per 32 columns
         p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
         assert (p["kernel"], p["column_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 128, 128)
+    for T in (65, 128):                                                 # up to 128 tokens while every slice has a CU
+        p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
+        assert (p["kernel"], p["tile_tokens"], p["tile_columns"], p["workgroups"]) == (bda.KERNEL_DECODE, 128, 32, 128)
+        assert _plan(T, [40, 40], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_LEAN      # 320 slices: tiles
+    p = _plan(64, [128, 128], [0, 0], bda.BDA_BF16)                     # wide output: 128-column slices
+    assert (p["kernel"], p["tile_columns"], p["workgroups"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 128, 256, 144 * 1024)
+    p = _plan(16, [128, 128], [0, 0], bda.BDA_BF16)
+    assert (p["kernel"], p["tile_tokens"], p["tile_columns"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 32, 128, 120 * 1024)
+    assert _plan(64, [64, 64], [0, 0], bda.BDA_BF16)["tile_columns"] == 32       # 128 slices of 128: stays with 32-column slices
+    assert _plan(64, [128, 128], [0, 0], bda.BDA_BF16, d_c=1024)["tile_columns"] == 32   # K = 896 > 384
     p = bda.bda_dense_project_plan(8192, 4096, 1024, bda.BDA_F16)       # BD linear, first GEMM
     assert (p["kernel"], p["tile_tokens"], p["token_tiles"] * p["column_tiles"], p["rounds"]) == (bda.KERNEL_LEAN, 128, 256, 1)
     p = _plan(64, [1], [0], bda.BDA_F32, d_c=64, d_h=32)                # config 1: float32
@@ -236,7 +246,7 @@ def test_launch_plan_benchmark_shapes():
 def test_launch_plan_tile_choice_by_rounds():
     """128-token tiles where they need fewer than 1/0.56 times the rounds of 256-token tiles; dies
     take single tiles where whole super-tiles would need more rounds."""
-    want = {100: (128, 1, 0), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
+    want = {200: (128, 1, 0), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
             3072: (256, 1, 1), 4096: (256, 1, 0), 5120: (128, 3, 0), 8192: (256, 2, 0)}
     for T, (tokens, rounds, by_tile) in want.items():
         p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
