@@ -44,6 +44,22 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
     const int nks = (p.K + 15) >> 4;                     // k-steps of 16
     const int wgt_bytes = nks * 16 * 64;                 // LDS: [k][32 columns] 16-bit
 
+    // ---- identity values of the columns this wave finishes (8 wave + 4 lhi + 0..3), requested first
+    // so that the epilogue does not wait for them ----------------------------------------------------
+    const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    const int ep_col = 8 * wave + 4 * lhi;
+    u32x2 idv[NTB];
+    if (p.ident) {
+        const int j = (rel0 + ep_col) % p.d_h;
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb)
+            idv[tb] = __builtin_amdgcn_raw_buffer_load_b64(
+                rA, ep_col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+    } else {
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) idv[tb] = (u32x2){0u, 0u};
+    }
+
     // ---- the slice of C: K rows x 64 bytes, 16 rows per DMA instruction --------------------------
     const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
     {
@@ -60,7 +76,6 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
 
     // ---- token fragments for this wave's k-steps (ks = wave, wave + 4, ...) --------------------------
     const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
-    const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
     f32x16 acc[NTB];
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb)
@@ -121,7 +136,7 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
             for (int r = 0; r < 16; ++r) part[((wave * NTB + tb) * 16 + r) * 64 + lane] = acc[tb][r];
     __syncthreads();
     // wave w finishes accumulator rows 4 w .. 4 w + 3 = output columns 8 w + 4 lhi + 0..3
-    const int col = 8 * wave + 4 * lhi;
+    const int col = ep_col;
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
                                                 ((int64_t)(T - 1) * p.ldd + cols_left) * (int64_t)sizeof(OutT));
 #pragma unroll
@@ -137,13 +152,10 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
         }
         const int t = tb * 32 + l31;
         if (p.ident) {
-            const int j = (rel0 + col) % p.d_h;
-            const u32x2 idv = __builtin_amdgcn_raw_buffer_load_b64(
-                rA, col < cols_left ? (uint32_t)t * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
-            v[0] += X::to_f32((uint16_t)(idv[0] & 0xffffu));
-            v[1] += X::to_f32((uint16_t)(idv[0] >> 16));
-            v[2] += X::to_f32((uint16_t)(idv[1] & 0xffffu));
-            v[3] += X::to_f32((uint16_t)(idv[1] >> 16));
+            v[0] += X::to_f32((uint16_t)(idv[tb][0] & 0xffffu));
+            v[1] += X::to_f32((uint16_t)(idv[tb][0] >> 16));
+            v[2] += X::to_f32((uint16_t)(idv[tb][1] & 0xffffu));
+            v[3] += X::to_f32((uint16_t)(idv[tb][1] >> 16));
         }
         const uint32_t off = col < cols_left ? (uint32_t)t * (uint32_t)(p.ldd * sizeof(OutT)) + (uint32_t)col * (uint32_t)sizeof(OutT) : kBadOffset;
         if constexpr (sizeof(OutT) == 4) {
@@ -200,6 +212,22 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
     const int T = (int)p.M;
     const int nks = (p.K + 15) >> 4;                     // <= kDecodeWideMaxKS (host contract)
     const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
+
+    // ---- identity values of this lane's results (token l31 of block tb, columns 32 wave + 8 q + 4 lhi
+    // + 0..3), requested first so that the epilogue does not wait for them ---------------------------
+    const __amdgpu_buffer_rsrc_t rI = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    u32x2 idv[NTB][4];
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = 32 * wave + 8 * q + 4 * lhi;
+            if (p.ident) {
+                const int j = (rel0 + col) % p.d_h;
+                idv[tb][q] = __builtin_amdgcn_raw_buffer_load_b64(
+                    rI, col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+            } else idv[tb][q] = (u32x2){0u, 0u};
+        }
 
     // ---- the token rows: [64-k stage][token][128 bytes] behind the slice of C, piece q of a row at
     // position q ^ tok_swz<64>(row); one request = 8 rows x 128 bytes, the waves take turns -----------
@@ -282,7 +310,6 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
     }
 
     // ---- epilogue: lane (token l31, half lhi) holds columns 32 wave + 8 q + 4 lhi + 0..3, q = 0..3 ---
-    const __amdgpu_buffer_rsrc_t rI = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
                                                 ((int64_t)(T - 1) * p.ldd + cols_left) * (int64_t)sizeof(OutT));
 #pragma unroll
@@ -294,13 +321,10 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
             const int col = 32 * wave + 8 * q + 4 * lhi;
             float v[4] = {acc[tb][4 * q], acc[tb][4 * q + 1], acc[tb][4 * q + 2], acc[tb][4 * q + 3]};
             if (p.ident) {
-                const int j = (rel0 + col) % p.d_h;
-                const u32x2 idv = __builtin_amdgcn_raw_buffer_load_b64(
-                    rI, col < cols_left ? (uint32_t)t * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
-                v[0] += X::to_f32((uint16_t)(idv[0] & 0xffffu));
-                v[1] += X::to_f32((uint16_t)(idv[0] >> 16));
-                v[2] += X::to_f32((uint16_t)(idv[1] & 0xffffu));
-                v[3] += X::to_f32((uint16_t)(idv[1] >> 16));
+                v[0] += X::to_f32((uint16_t)(idv[tb][q][0] & 0xffffu));
+                v[1] += X::to_f32((uint16_t)(idv[tb][q][0] >> 16));
+                v[2] += X::to_f32((uint16_t)(idv[tb][q][1] & 0xffffu));
+                v[3] += X::to_f32((uint16_t)(idv[tb][q][1] >> 16));
             }
             const uint32_t off = col < cols_left ? (uint32_t)t * (uint32_t)(p.ldd * sizeof(OutT)) + (uint32_t)col * (uint32_t)sizeof(OutT) : kBadOffset;
             if constexpr (sizeof(OutT) == 4) {
