@@ -296,6 +296,30 @@ def test_dense_project(dtype, policy):
     assert_parity(gh.to_host64(out_d, dtype), ref, 128, dtype, dtype, "dense")
 
 
+@pytest.mark.parametrize("T", [1, 40, 64, 100])
+@pytest.mark.parametrize("policy", [0, 5])
+def test_dense_project_few_tokens(T, policy):
+    """The small-T kernels without an identity slice: 32-column slices (policy 0; four token blocks
+    at T = 100) and 128-column slices (policy 5, up to 64 tokens), contraction 320."""
+    dtype = wl.BF16
+    w = wl.custom_kv_workload("dense_few", T=T, d_c=320, d_h=64, H=[9], std=0.05, rms_norm=True, dtype=dtype, seed=23 + T)
+    W_stored, W64 = wl.to_storage(w.W, dtype)
+    ref = oracle.dense_project(w.c, W64)
+    c_d, W_d = gh.to_device(w.c_stored, dtype), gh.to_device(W_stored, dtype)
+    out_d = gh.new_out(w.T, w.N, dtype)
+    p = bda.bda_dense_project_plan(T, 320, w.N, dtype)
+    assert p["kernel"] == bda.KERNEL_DECODE
+    bda.bda_set_tile_policy(policy)
+    try:
+        if policy == 5 and T <= 64:
+            assert bda.bda_dense_project_plan(T, 320, w.N, dtype)["tile_columns"] == 128
+        bda.bda_dense_project(c_d, 320, w.T, 320, W_d, w.N, w.N, out_d, w.N, dtype, stream=gh.stream())
+    finally:
+        bda.bda_set_tile_policy(0)
+    torch.cuda.synchronize()
+    assert_parity(gh.to_host64(out_d, dtype), ref, 64, dtype, dtype, "dense few tokens")
+
+
 @pytest.mark.parametrize("last", [False, True])
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
 def test_lowrank_linear_small(last, dtype):
