@@ -13,15 +13,82 @@
 //   * the token fragments come straight from global memory in MFMA operand layout (a row of the
 //     latent is k-contiguous), the identity slice is added in float32 after the reduction.
 #pragma once
+#include <type_traits>
+
 #include "bda_gemm_stream.hpp"
 
 namespace bda {
 
 constexpr int kDecodeMaxT = 128;
+
+// s_waitcnt vmcnt(n) for a run-time n (even, <= 26): the largest immediate that is not above n.
+__device__ __forceinline__ void wait_vmcnt_at_most(int n)
+{
+    if (n >= 26) wait_vmcnt<26>();
+    else if (n >= 24) wait_vmcnt<24>();
+    else if (n >= 22) wait_vmcnt<22>();
+    else if (n >= 20) wait_vmcnt<20>();
+    else if (n >= 18) wait_vmcnt<18>();
+    else if (n >= 16) wait_vmcnt<16>();
+    else if (n >= 14) wait_vmcnt<14>();
+    else if (n >= 12) wait_vmcnt<12>();
+    else if (n >= 10) wait_vmcnt<10>();
+    else if (n >= 8) wait_vmcnt<8>();
+    else if (n >= 6) wait_vmcnt<6>();
+    else if (n >= 4) wait_vmcnt<4>();
+    else if (n >= 2) wait_vmcnt<2>();
+    else wait_vmcnt<0>();
+}
+
+// Group of a column slice and that group's table entries.  Every table entry is read whatever the
+// slice (one batch of scalar loads from the kernel arguments, no load depends on another) and the
+// entries wanted are picked by comparison: the chain from kernel start to the first request for C
+// is what a launch with a few tokens waits for.
+struct SliceGroup { int tile0; int64_t col0, col1; int a_off; };
+__device__ __forceinline__ SliceGroup slice_group(const GemmArgs& p, int slice)
+{
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroups; ++i) g += (i < p.n_groups && slice >= p.tile_start[i]) ? 1 : 0;
+    SliceGroup r = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < kMaxGroups; ++i) {
+        const bool hit = g == i;
+        r.tile0 = hit ? p.tile_start[i] : r.tile0;
+        r.col0 = hit ? p.col_start[i] : r.col0;
+        r.col1 = hit ? p.col_start[i + 1] : r.col1;
+        r.a_off = hit ? p.a_off[i] : r.a_off;
+    }
+    return r;
+}
 constexpr int kDecodeMaxK = 1536;       // K x 64 bytes of LDS for the slice of C
 
+// Every kernel argument a small-T kernel uses, the slice of this workgroup and its group's table
+// entries, read in one batch of scalar loads at kernel start and pinned to registers there: three
+// dependent trips to the argument block (tile count, tables, pitches) were about a tenth of such a
+// launch.
+struct DecodeArgs {
+    const void *A, *B; void* D;
+    int64_t lda, ldb, ldd, M;
+    int K, d_h, a_skip, ident, n_tiles, slice;
+    SliceGroup sg;
+};
+__device__ __forceinline__ DecodeArgs decode_args(const GemmArgs& p)
+{
+    DecodeArgs q = {p.A, p.B, p.D, p.lda, p.ldb, p.ldd, p.M, p.K, p.d_h, p.a_skip, p.ident, p.n_tiles, 0, {0, 0, 0, 0}};
+    // dies take contiguous runs of slices
+    const int per_xcd = (q.n_tiles + kNumXcd - 1) / kNumXcd;
+    q.slice = (int)(blockIdx.x % kNumXcd) * per_xcd + (int)(blockIdx.x / kNumXcd);
+    q.sg = slice_group(p, q.slice);
+    asm volatile("" : "+s"(q.A), "+s"(q.B), "+s"(q.D), "+s"(q.lda), "+s"(q.ldb), "+s"(q.ldd), "+s"(q.M),
+                 "+s"(q.sg.col0), "+s"(q.sg.col1));
+    asm volatile("" : "+s"(q.K), "+s"(q.d_h), "+s"(q.a_skip), "+s"(q.ident), "+s"(q.n_tiles), "+s"(q.slice),
+                 "+s"(q.sg.tile0), "+s"(q.sg.a_off));
+    return q;
+}
+
 template <typename X, typename OutT, int NTB>
-__global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
+__global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int tid = threadIdx.x;
@@ -29,38 +96,22 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, lhi = lane >> 5;
 
-    // slice owned by this workgroup: dies take contiguous runs of slices
-    const int per_xcd = (p.n_tiles + kNumXcd - 1) / kNumXcd;
-    const int slice = (int)(blockIdx.x % kNumXcd) * per_xcd + (int)(blockIdx.x / kNumXcd);
+    // slice owned by this workgroup
+    const DecodeArgs p = decode_args(p_in);
+    const int slice = p.slice;
     if (slice >= p.n_tiles) return;
-    int g = 0;
-    while (g + 1 < p.n_groups && slice >= p.tile_start[g + 1]) ++g;
-    const int rel0 = (slice - p.tile_start[g]) * 32;
-    const int64_t n0 = p.col_start[g] + rel0;
-    const int64_t left = p.col_start[g + 1] - n0;
+    const SliceGroup sg = p.sg;
+    const int rel0 = (slice - sg.tile0) * 32;
+    const int64_t n0 = sg.col0 + rel0;
+    const int64_t left = sg.col1 - n0;
     const int cols_left = (int)(left > 32 ? 32 : left);
-    const int a_off = p.a_off[g];
+    const int a_off = sg.a_off;
     const int T = (int)p.M;
     const int nks = (p.K + 15) >> 4;                     // k-steps of 16
     const int wgt_bytes = nks * 16 * 64;                 // LDS: [k][32 columns] 16-bit
 
-    // ---- identity values of the columns this wave finishes (8 wave + 4 lhi + 0..3), requested first
-    // so that the epilogue does not wait for them ----------------------------------------------------
-    const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
-    const int ep_col = 8 * wave + 4 * lhi;
-    u32x2 idv[NTB];
-    if (p.ident) {
-        const int j = (rel0 + ep_col) % p.d_h;
-#pragma unroll
-        for (int tb = 0; tb < NTB; ++tb)
-            idv[tb] = __builtin_amdgcn_raw_buffer_load_b64(
-                rA, ep_col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
-    } else {
-#pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) idv[tb] = (u32x2){0u, 0u};
-    }
-
-    // ---- the slice of C: K rows x 64 bytes, 16 rows per DMA instruction --------------------------
+    // ---- the slice of C: K rows x 64 bytes, 16 rows per DMA instruction (first of all: everything
+    // else the kernel does before its MFMAs hides behind this request) --------------------------------
     const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
     {
         const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
@@ -76,6 +127,9 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
 
     // ---- token fragments for this wave's k-steps (ks = wave, wave + 4, ...) --------------------------
     const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
+    const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    const int ep_col = 8 * wave + 4 * lhi;               // this wave finishes columns 8 wave + 4 lhi + 0..3
+    u32x2 idv[NTB];
     f32x16 acc[NTB];
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb)
@@ -89,6 +143,21 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
 
+    // identity values of the columns this wave finishes, wanted only in the epilogue: requested
+    // behind the first token fragments; returns whether there were requests
+    auto load_identity = [&]() -> bool {
+        if (p.ident) {
+            const int j = (rel0 + ep_col) % p.d_h;
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb)
+                idv[tb] = __builtin_amdgcn_raw_buffer_load_b64(
+                    rA, ep_col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+        } else {
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) idv[tb] = (u32x2){0u, 0u};
+        }
+        return p.ident != 0;
+    };
     // first the token loads of all this wave's k-steps (they overlap the DMA), in chunks of 6 k-steps
     for (int ks0 = wave; ks0 < nks; ks0 += 4 * 6) {
         u32x4 ft[6][NTB];
@@ -104,25 +173,28 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p)
                     rA, ok ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset, 0, 0);
             }
         }
-        if (ks0 == wave) {                                // the slice of C must have landed (all waves)
-            wait_vmcnt<6 * NTB>();                        // the token loads above may still fly
+        if (ks0 == wave) {
+            // the slice of C must have landed (all waves); the loads issued after it may still fly
+            if (load_identity()) wait_vmcnt<7 * NTB>(); else wait_vmcnt<6 * NTB>();
             __syncthreads();
         }
+        // the chunk's fragments of C first, then its MFMAs (k-steps past K read rows of zeros)
+        u32x4 fw[6];
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
-            const int ks = ks0 + 4 * i;
-            if (ks < nks) {
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024 + 256));
-                const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-                const u32x4 fw = {lo2[0], lo2[1], hi2[0], hi2[1]};
-#pragma unroll
-                for (int tb = 0; tb < NTB; ++tb)           // (blocks past T hold zeros)
-                    acc[tb] = X::mfma(fw, ft[i][tb], acc[tb]);
-            }
+            const int ks = ks0 + 4 * i < nks ? ks0 + 4 * i : nks - 1;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024 + 256));
+            const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+            fw[i] = (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
         }
+#pragma unroll
+        for (int i = 0; i < 6; ++i)                        // (token fragments past K or T hold zeros)
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) acc[tb] = X::mfma(fw[i], ft[i][tb], acc[tb]);
     }
     if (wave >= nks) {                                    // a wave without k-steps still joins the barrier
+        load_identity();
         wait_vmcnt<0>();
         __syncthreads();
     }
@@ -190,7 +262,7 @@ constexpr int kDecodeWideMaxKS = 24;    // k-steps of 16: K <= 384
 constexpr int kDecodeWideCols = 128;
 
 template <typename X, typename OutT, int NTB>
-__global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
+__global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     constexpr int CH = 6;                                 // k-steps per chunk (four chunks)
@@ -199,39 +271,46 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, lhi = lane >> 5;
 
-    const int per_xcd = (p.n_tiles + kNumXcd - 1) / kNumXcd;
-    const int slice = (int)(blockIdx.x % kNumXcd) * per_xcd + (int)(blockIdx.x / kNumXcd);
+    const DecodeArgs p = decode_args(p_in);
+    const int slice = p.slice;
     if (slice >= p.n_tiles) return;
-    int g = 0;
-    while (g + 1 < p.n_groups && slice >= p.tile_start[g + 1]) ++g;
-    const int rel0 = (slice - p.tile_start[g]) * kDecodeWideCols;
-    const int64_t n0 = p.col_start[g] + rel0;
-    const int64_t left = p.col_start[g + 1] - n0;
+    const SliceGroup sg = p.sg;
+    const int rel0 = (slice - sg.tile0) * kDecodeWideCols;
+    const int64_t n0 = sg.col0 + rel0;
+    const int64_t left = sg.col1 - n0;
     const int cols_left = (int)(left > kDecodeWideCols ? kDecodeWideCols : left);
-    const int a_off = p.a_off[g];
+    const int a_off = sg.a_off;
     const int T = (int)p.M;
     const int nks = (p.K + 15) >> 4;                     // <= kDecodeWideMaxKS (host contract)
     const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
+    const int issued = (nks + 1) & ~1;                   // requests per wave for C: one per k-step, a filler for an odd count
 
-    // ---- identity values of this lane's results (token l31 of block tb, columns 32 wave + 8 q + 4 lhi
-    // + 0..3), requested first so that the epilogue does not wait for them ---------------------------
-    const __amdgpu_buffer_rsrc_t rI = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
-    u32x2 idv[NTB][4];
+    // ---- the slice of C: wave w requests rows 16 ks + 4 w .. + 3 of every k-step, in k order; the
+    // first chunk's requests go out before anything else, the rest behind the token rows -------------
+    const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
+    const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
+    uint32_t c_lane_off;
+    {
+        const int r = lane >> 4;                                      // row within the instruction = row & 3
+        const int piece = (lane & 15) ^ (4 * r);                      // global piece held at LDS position lane & 15
+        c_lane_off = piece * 8 < cols_left ? (uint32_t)(4 * wave + r) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
+    }
+    const uint32_t c_lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u;
+    auto request_c = [&](auto first, auto last) {                     // k-steps [first, last), two at a time
 #pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int col = 32 * wave + 8 * q + 4 * lhi;
-            if (p.ident) {
-                const int j = (rel0 + col) % p.d_h;
-                idv[tb][q] = __builtin_amdgcn_raw_buffer_load_b64(
-                    rI, col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
-            } else idv[tb][q] = (u32x2){0u, 0u};
+        for (int ks = decltype(first)::value; ks < decltype(last)::value; ks += 2) {   // rows past K fall outside rB's range -> zeros
+            if (ks < nks) {
+                const uint32_t v0 = c_lane_off + (uint32_t)(ks * 16) * row_bytes;
+                const uint32_t v1 = ks + 1 < nks ? c_lane_off + (uint32_t)((ks + 1) * 16) * row_bytes : kBadOffset;
+                lds_dma1(rB, c_lds0 + (uint32_t)ks * 4096u, v0);
+                lds_dma1(rB, c_lds0 + (uint32_t)(ks + 1) * 4096u, v1);
+            }
         }
+    };
+    request_c(std::integral_constant<int, 0>{}, std::integral_constant<int, CH>{});
 
     // ---- the token rows: [64-k stage][token][128 bytes] behind the slice of C, piece q of a row at
     // position q ^ tok_swz<64>(row); one request = 8 rows x 128 bytes, the waves take turns -----------
-    const int issued = (nks + 1) & ~1;                   // requests per wave for C: one per k-step, a filler for an odd count
     const int n_st = (p.K + 63) >> 6;
     const uint32_t tok_lds = (uint32_t)issued * 4096u;
     const u32x4 rA = make_rsrc_words(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
@@ -247,25 +326,24 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
                      row < T && k < p.K ? (uint32_t)row * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset);
         }
     }
+    request_c(std::integral_constant<int, CH>{}, std::integral_constant<int, kDecodeWideMaxKS>{});
 
-    // ---- the slice of C: wave w requests rows 16 ks + 4 w .. + 3 of every k-step, in k order -------
-    const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
-    {
-        const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
-        const int r = lane >> 4;                                      // row within the instruction = row & 3
-        const int piece = (lane & 15) ^ (4 * r);                      // global piece held at LDS position lane & 15
-        const uint32_t lane_off = piece * 8 < cols_left ? (uint32_t)(4 * wave + r) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u;
+    // ---- identity values of this lane's results (token l31 of block tb, columns 32 wave + 8 q + 4 lhi
+    // + 0..3), wanted only in the epilogue: requested last --------------------------------------------
+    const __amdgpu_buffer_rsrc_t rI = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+    u32x2 idv[NTB][4];
 #pragma unroll
-        for (int ks = 0; ks < kDecodeWideMaxKS; ks += 2) {            // rows past K fall outside rB's range -> zeros
-            if (ks < nks) {
-                const uint32_t v0 = lane_off + (uint32_t)(ks * 16) * row_bytes;
-                const uint32_t v1 = ks + 1 < nks ? lane_off + (uint32_t)((ks + 1) * 16) * row_bytes : kBadOffset;
-                lds_dma1(rB, lds0 + (uint32_t)ks * 4096u, v0);
-                lds_dma1(rB, lds0 + (uint32_t)(ks + 1) * 4096u, v1);
-            }
+    for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = 32 * wave + 8 * q + 4 * lhi;
+            if (p.ident) {
+                const int j = (rel0 + col) % p.d_h;
+                idv[tb][q] = __builtin_amdgcn_raw_buffer_load_b64(
+                    rI, col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+            } else idv[tb][q] = (u32x2){0u, 0u};
         }
-    }
+    const int n_idv = p.ident ? 4 * NTB : 0;
 
     f32x16 acc[NTB];
 #pragma unroll
@@ -287,14 +365,12 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p)
                           + (uint32_t)(l31 * 128 + ((lhi ^ tok_swz<64>(l31 & 15)) << 4));
 
     // ---- four chunks of six k-steps: wait for this wave's requests of the chunk, meet the others ---
-    // (the token requests were issued first, so they are complete whenever a request for C is)
+    // (the counter is in order: the token requests follow the first chunk's, so whatever may still
+    // fly at chunk c are the requests for C of later chunks and the identity values)
 #pragma unroll
     for (int c = 0; c < kDecodeWideMaxKS / CH; ++c) {
-        const int rem = issued - CH * (c + 1);            // requests of later chunks may still fly
-        if (rem >= 18) wait_vmcnt<18>();
-        else if (rem >= 12) wait_vmcnt<12>();
-        else if (rem >= 6) wait_vmcnt<6>();
-        else wait_vmcnt<0>();
+        const int later = issued - CH * (c + 1);
+        wait_vmcnt_at_most((later > 0 ? later : 0) + n_idv);
         __syncthreads();
         const int ks_end = nks < CH * (c + 1) ? nks : CH * (c + 1);
         for (int ks = CH * c; ks < ks_end; ++ks) {       // (a plain loop: the accumulators stay where they are)
