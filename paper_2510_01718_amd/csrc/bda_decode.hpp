@@ -200,12 +200,17 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
     }
 
     // ---- fixed-order reduction over the four waves ------------------------------------------------
-    float* part = (float*)(smem + wgt_bytes);            // [wave][tb][r][lane]
+    // partial sums in LDS: [wave][tb][lane][4 groups of 4 accumulator rows], group q of lane l at
+    // position q ^ (l / 4 % 4) (16-byte accesses of neighbouring lanes then fall into different banks)
+    f32x4* part = (f32x4*)(smem + wgt_bytes);
+    const int part_swz = (lane >> 2) & 3;
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb)
         if (tb < n_tb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) part[((wave * NTB + tb) * 16 + r) * 64 + lane] = acc[tb][r];
+            for (int q = 0; q < 4; ++q)
+                part[((wave * NTB + tb) * 64 + lane) * 4 + (q ^ part_swz)] =
+                    (f32x4){acc[tb][4 * q], acc[tb][4 * q + 1], acc[tb][4 * q + 2], acc[tb][4 * q + 3]};
     __syncthreads();
     // wave w finishes accumulator rows 4 w .. 4 w + 3 = output columns 8 w + 4 lhi + 0..3
     const int col = ep_col;
@@ -214,14 +219,12 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb) {
         if (tb >= n_tb) break;
+        f32x4 pw[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) pw[w] = part[((w * NTB + tb) * 64 + lane) * 4 + (wave ^ part_swz)];
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float s = 0.0f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) s += part[((w * NTB + tb) * 16 + 4 * wave + e) * 64 + lane];
-            v[e] = s;
-        }
+        for (int e = 0; e < 4; ++e) v[e] = ((pw[0][e] + pw[1][e]) + pw[2][e]) + pw[3][e];   // fixed order
         const int t = tb * 32 + l31;
         if (p.ident) {
             v[0] += X::to_f32((uint16_t)(idv[tb][0] & 0xffffu));
