@@ -147,11 +147,13 @@ int launch_decode_wide(GemmArgs& a, hipStream_t st)
     return a.M <= 32 ? launch_decode_wide_blocks<X, OutT, 1>(a, st) : launch_decode_wide_blocks<X, OutT, 2>(a, st);
 }
 
-// Two blocks of 32 token rows per workgroup up to 64 tokens, four up to 128.
+// One block of 32 token rows per workgroup up to 32 tokens, two up to 64, four up to 128.
 template <typename X, typename OutT>
 int launch_decode(GemmArgs& a, hipStream_t st)
 {
-    return a.M <= 64 ? launch_decode_blocks<X, OutT, 2>(a, st) : launch_decode_blocks<X, OutT, 4>(a, st);
+    return a.M <= 32   ? launch_decode_blocks<X, OutT, 1>(a, st)
+           : a.M <= 64 ? launch_decode_blocks<X, OutT, 2>(a, st)
+                       : launch_decode_blocks<X, OutT, 4>(a, st);
 }
 
 template <typename InT, typename OutT>

@@ -1,5 +1,5 @@
 // Small-T ("decode") kernel of libbda for gfx950: T <= 128 tokens (NTB blocks of 32 token rows per
-// workgroup: 2 for T <= 64, 4 above).
+// workgroup: 1 for T <= 32, 2 for T <= 64, 4 above).
 //
 // With a handful of tokens the projection is a stream over the weights: every element of C is read
 // exactly once and used for at most 128 multiply-adds, so the kernel is organised around that read
