@@ -111,16 +111,25 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
 
-template <typename X, typename OutT, int NTB>
+// LDS of the 32-column small-T kernel: slice of C, token rows (TOK_LDS), float32 partial sums of the
+// four waves (in the token rows' space when there are two token blocks).
+template <int NTB, bool TOK_LDS>
+int decode_lds_bytes(int K)
+{
+    const int wgt = ((K + 15) / 16) * 1024, part = NTB * 16384;
+    const int tok = TOK_LDS ? ((K + 63) / 64) * NTB * 4096 : 0;
+    return (TOK_LDS && NTB == 2) ? wgt + std::max(tok, part) : wgt + tok + part;
+}
+
+template <typename X, typename OutT, int NTB, bool TOK_LDS>
 int launch_decode_blocks(GemmArgs& a, hipStream_t st)
 {
     static std::once_flag once;
-    auto kern = kv_decode_kernel<X, OutT, NTB>;
-    const int part = NTB * 16384;                           // float32 partial sums of the four waves
-    const int lds = ((a.K + 15) / 16) * 1024 + part;
+    auto kern = kv_decode_kernel<X, OutT, NTB, TOK_LDS>;
+    const int lds = decode_lds_bytes<NTB, TOK_LDS>(a.K);
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
     if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, 32, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
-    if (int rc = set_max_lds(kern, kDecodeMaxK * 64 + part, once)) return rc;
+    if (int rc = set_max_lds(kern, decode_lds_bytes<NTB, TOK_LDS>(TOK_LDS ? kDecodeTokLdsMaxK : kDecodeMaxK), once)) return rc;
     hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
@@ -151,9 +160,12 @@ int launch_decode_wide(GemmArgs& a, hipStream_t st)
 template <typename X, typename OutT>
 int launch_decode(GemmArgs& a, hipStream_t st)
 {
-    return a.M <= 32   ? launch_decode_blocks<X, OutT, 1>(a, st)
-           : a.M <= 64 ? launch_decode_blocks<X, OutT, 2>(a, st)
-                       : launch_decode_blocks<X, OutT, 4>(a, st);
+    // Token rows through LDS for 33 .. 64 tokens (measured, V2-Lite shape, us: 64 tokens 5.2 against 5.6
+    // with fragments from global memory; 32 tokens level; 1 .. 8 tokens 4.4-4.5 against 4.0-4.1: there
+    // the extra wait-for-everything costs more than the cheaper loads save).
+    if (a.M <= 32) return launch_decode_blocks<X, OutT, 1, false>(a, st);
+    if (a.M <= 64) return a.K <= kDecodeTokLdsMaxK ? launch_decode_blocks<X, OutT, 2, true>(a, st) : launch_decode_blocks<X, OutT, 2, false>(a, st);
+    return launch_decode_blocks<X, OutT, 4, false>(a, st);
 }
 
 template <typename InT, typename OutT>

@@ -62,6 +62,7 @@ __device__ __forceinline__ SliceGroup slice_group(const GemmArgs& p, int slice)
     return r;
 }
 constexpr int kDecodeMaxK = 1536;       // K x 64 bytes of LDS for the slice of C
+constexpr int kDecodeTokLdsMaxK = 512;  // up to here (and 64 tokens) the token rows go through LDS as well
 
 // Every kernel argument a small-T kernel uses, the slice of this workgroup and its group's table
 // entries, read in one batch of scalar loads at kernel start and pinned to registers there: three
@@ -87,7 +88,13 @@ __device__ __forceinline__ DecodeArgs decode_args(const GemmArgs& p)
     return q;
 }
 
-template <typename X, typename OutT, int NTB>
+// TOK_LDS (used for 33 .. 64 tokens with K <= 512): the token rows go through LDS like the slice of C,
+// requested as full 128-byte pieces (8 rows per instruction) instead of as MFMA fragments straight
+// from global memory (32 rows x 32 bytes per instruction, which costs four times the address work:
+// with 64 tokens those loads were what a launch waited for).  LDS then holds [slice of C][token rows:
+// 64-k stage, token, 128 bytes, swizzled like the streaming kernel's token stages][partial sums];
+// with two token blocks the partial sums reuse the token rows' space (one more barrier).
+template <typename X, typename OutT, int NTB, bool TOK_LDS>
 __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -158,6 +165,51 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
         }
         return p.ident != 0;
     };
+    constexpr bool PART_ALIAS = TOK_LDS && NTB == 2;
+    const int n_st = (p.K + 63) >> 6;
+    const int tok_bytes = TOK_LDS ? n_st * NTB * 4096 : 0;
+    if constexpr (TOK_LDS) {
+        // token rows: one request = 8 rows x 128 bytes, the waves take turns; then the identity values;
+        // all of it and the slice of C must have landed before anybody multiplies
+        const u32x4 rAw = make_rsrc_words(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
+        const int row8 = lane >> 3;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wgt_bytes;
+        const int n_req = n_st * NTB * 4;
+        for (int i = wave; i < n_req; i += 4) {           // request i: stage i / (4 NTB), rows 8 (i % (4 NTB)) .. + 7
+            const int st = i / (4 * NTB), row = 8 * (i % (4 * NTB)) + row8;
+            const int k = 64 * st + 8 * ((lane & 7) ^ tok_swz<64>(row & 15));
+            const int col = k < a_off ? k : k + p.a_skip;
+            lds_dma1(rAw, lds0 + (uint32_t)i * 1024u,
+                     row < T && k < p.K ? (uint32_t)row * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset);
+        }
+        if (load_identity()) wait_vmcnt<NTB>(); else wait_vmcnt<0>();
+        __syncthreads();
+        typedef __attribute__((address_space(3))) const u32x4* lds_u32x4;
+        const uint32_t t_rd = lds0 + (uint32_t)(l31 * 128 + ((lhi ^ tok_swz<64>(l31 & 15)) << 4));
+        for (int ks0 = wave; ks0 < nks; ks0 += 4 * 6) {   // chunks of six of this wave's k-steps: fragments first, then MFMAs
+            u32x4 fw[6], ft[6][NTB];
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                const bool ok = ks0 + 4 * i < nks;
+                const int ks = ok ? ks0 + 4 * i : nks - 1;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 1024 + 256));
+                const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+                fw[i] = (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
+                const uint32_t ta = (t_rd + (uint32_t)((ks >> 2) * (NTB * 4096))) ^ (uint32_t)((ks & 3) << 5);
+#pragma unroll
+                for (int tb = 0; tb < NTB; ++tb) {
+                    const u32x4 t = *(lds_u32x4)(uintptr_t)(ta + tb * 4096);
+                    ft[i][tb] = ok ? t : (u32x4){0u, 0u, 0u, 0u};          // a k-step past K adds nothing
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 6; ++i)
+#pragma unroll
+                for (int tb = 0; tb < NTB; ++tb) acc[tb] = X::mfma(fw[i], ft[i][tb], acc[tb]);
+        }
+        if constexpr (PART_ALIAS) __syncthreads();        // the partial sums overwrite the token rows
+    } else {
     // first the token loads of all this wave's k-steps (they overlap the DMA), in chunks of 6 k-steps
     for (int ks0 = wave; ks0 < nks; ks0 += 4 * 6) {
         u32x4 ft[6][NTB];
@@ -198,11 +250,12 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
         wait_vmcnt<0>();
         __syncthreads();
     }
+    }
 
     // ---- fixed-order reduction over the four waves ------------------------------------------------
     // partial sums in LDS: [wave][tb][lane][4 groups of 4 accumulator rows], group q of lane l at
     // position q ^ (l / 4 % 4) (16-byte accesses of neighbouring lanes then fall into different banks)
-    f32x4* part = (f32x4*)(smem + wgt_bytes);
+    f32x4* part = (f32x4*)(smem + wgt_bytes + (PART_ALIAS ? 0 : tok_bytes));
     const int part_swz = (lane >> 2) & 3;
 #pragma unroll
     for (int tb = 0; tb < NTB; ++tb)
