@@ -5,13 +5,17 @@
 // exactly once and used for at most 128 multiply-adds, so the kernel is organised around that read
 // (bandwidth / latency bound), not around MFMA occupancy:
 //   * one workgroup per 32-column slice of the output, all K rows of it: its part of C
-//     (K x 64 bytes) goes global -> LDS in one burst of LDS DMA loads issued at kernel start;
+//     (K x 64 bytes) goes global -> LDS in one burst of LDS DMA loads, which are the first thing the
+//     kernel issues (all arguments and group tables come in one batch of scalar loads; token
+//     fragments and identity values are requested while C is on its way);
 //   * slices are handed out so that neighbouring slices (which share 128-byte lines of C) run on
 //     the same die and meet in its L2;
 //   * the four waves split the k-steps; their partial sums are added in a fixed order through LDS,
 //     so the result does not depend on scheduling;
 //   * the token fragments come straight from global memory in MFMA operand layout (a row of the
-//     latent is k-contiguous), the identity slice is added in float32 after the reduction.
+//     latent is k-contiguous) or, for 33 .. 64 tokens, through LDS; the identity slice is added in
+//     float32 after the reduction.
+// A second kernel at the end of this file gives a workgroup 128 columns, for wide outputs.
 #pragma once
 #include <type_traits>
 
