@@ -135,25 +135,29 @@ int launch_decode_blocks(GemmArgs& a, hipStream_t st)
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
 
-template <typename X, typename OutT, int NTB>
+template <typename X, typename OutT, int NTB, int CW>
 int launch_decode_wide_blocks(GemmArgs& a, hipStream_t st)
 {
     static std::once_flag once;
-    auto kern = kv_decode_wide_kernel<X, OutT, NTB>;
+    auto kern = kv_decode_wide_kernel<X, OutT, NTB, CW>;
+    constexpr int kspr = CW == 128 ? 1 : 2;                 // k-steps per request round
     const int nks = (a.K + 15) / 16;
-    const int lds = ((nks + 1) & ~1) * 4096 + ((a.K + 63) / 64) * NTB * 4096;   // slice of C, token rows
+    const int lds = ((nks + kspr - 1) / kspr) * 4096 + ((a.K + 63) / 64) * NTB * 4096;   // slice of C, token rows
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
-    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, kDecodeWideCols, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
-    if (int rc = set_max_lds(kern, kDecodeWideMaxKS * 4096 + (kDecodeWideMaxKS / 4) * NTB * 4096, once)) return rc;
+    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, CW, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
+    if (int rc = set_max_lds(kern, (kDecodeWideMaxKS / kspr) * 4096 + (kDecodeWideMaxKS / 4) * NTB * 4096, once)) return rc;
     hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
 
+// 128-column slices up to 64 tokens, 64-column slices (four token blocks) up to 128.
 template <typename X, typename OutT>
 int launch_decode_wide(GemmArgs& a, hipStream_t st)
 {
-    return a.M <= 32 ? launch_decode_wide_blocks<X, OutT, 1>(a, st) : launch_decode_wide_blocks<X, OutT, 2>(a, st);
+    if (a.M <= 32) return launch_decode_wide_blocks<X, OutT, 1, 128>(a, st);
+    if (a.M <= 64) return launch_decode_wide_blocks<X, OutT, 2, 128>(a, st);
+    return launch_decode_wide_blocks<X, OutT, 4, 64>(a, st);
 }
 
 // One block of 32 token rows per workgroup up to 32 tokens, two up to 64, four up to 128.
@@ -240,15 +244,18 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     // against 10.6) and loses beyond.
     const int policy0 = g_tile_policy.load();
     const bool small_policy = policy0 == 0 || policy0 == 5;
-    int64_t n_slices128 = 0, n_slices32 = 0;
+    int64_t n_slices128 = 0, n_slices64 = 0, n_slices32 = 0;
     for (int g = 0; g < G; ++g) {
-        n_slices128 += (group_cols[g] + kDecodeWideCols - 1) / kDecodeWideCols;
+        n_slices128 += (group_cols[g] + 127) / 128;
+        n_slices64 += (group_cols[g] + 63) / 64;
         n_slices32 += (group_cols[g] + 31) / 32;
     }
-    if (fast && ident_vec && a.M <= kDecodeWideMaxT && a.K <= 16 * kDecodeWideMaxKS
-        && (policy0 == 5 || (policy0 == 0 && n_slices128 >= 160))) {
-        // a few tokens, wide output: stream the weights once, 128 output columns per workgroup
-        build_tiles(a, G, group_cols, kDecodeWideMaxT, kDecodeWideCols);
+    // (65 .. 128 tokens: the 64-column slices where the 32-column ones would not have a compute unit each but these
+    // do: N = 12288 .. 16384 takes 8.4-9.4 us against 10.7-11.0 with 128-token tiles; wider outputs are left to the tiles)
+    const bool wide_auto = a.M <= 64 ? n_slices128 >= 160 : (n_slices32 > 256 && n_slices64 <= 256);
+    if (fast && ident_vec && a.M <= kDecodeMaxT && a.K <= 16 * kDecodeWideMaxKS && (policy0 == 5 || (policy0 == 0 && wide_auto))) {
+        // a few tokens, wide output: stream the weights once, 128 (64) output columns per workgroup
+        build_tiles(a, G, group_cols, kDecodeMaxT, a.M <= 64 ? 128 : 64);
         a.sm = a.sn = 1;
         if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_decode_wide<F16, uint16_t>(a, st);
         if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_decode_wide<F16, float>(a, st);

@@ -303,71 +303,77 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Wide-slice variant for T <= 64 and K <= 384: one workgroup per 128-column slice of the output.
+// Wide-slice variant for K <= 384: one workgroup per 128-column slice of the output (up to 64 tokens)
+// or per 64-column slice (up to 128 tokens).
 //
 // The 32-column kernel above needs N / 32 workgroups, which for a wide projection is several per
 // compute unit one after the other, each with its own burst, reduction and tail.  Here a workgroup
-// takes 128 columns (K x 256 bytes of C, up to 96 KiB in flight per compute unit from the first
-// instruction on), each of its four waves owns 32 of them for the whole of K, so there is no
-// reduction between waves, and the MFMAs of a quarter of the k-steps start as soon as that quarter
-// of the slice has landed.
-//   * C slice in LDS: [k][256 bytes]; the 16-byte pieces of row k sit at position piece ^ 4 (k & 3),
+// takes CW columns (K x 2 CW bytes of C, up to 96 KiB in flight per compute unit from the first
+// instruction on); its four waves are WC = CW / 32 along the columns times WT = 4 / WC along the
+// token blocks, each wave owns 32 columns and NTB / WT token blocks for the whole of K, so there
+// is no reduction between waves, and the MFMAs of a quarter of the k-steps start as soon as that
+// quarter of the slice has landed.
+//   * C slice in LDS: [k][2 CW bytes]; the 16-byte pieces of a row are XOR-swizzled by the row number
 //     so that the transposing reads of a wave (rows k .. k + 3, its own 64 bytes) hit 16 different
-//     pieces per 32 lanes;
-//   * the token rows go through LDS too (full 128-byte pieces per row and request, issued before the
-//     requests for C: they hit L2, and the in-order counter then covers them with the first chunk);
-//   * the identity slice is added in float32 from the latent, as above.
-constexpr int kDecodeWideMaxT = 64;
+//     pieces per 32 lanes (CW = 128: piece ^ 4 (k & 3); CW = 64: piece ^ 4 (k / 2 & 1));
+//   * the token rows go through LDS too (full 128-byte pieces per row and request, issued behind the
+//     first quarter's requests for C: they hit L2, and the in-order counter then covers them with it);
+//   * the identity slice is added in float32 from the latent, requested last, used in the epilogue.
 constexpr int kDecodeWideMaxKS = 24;    // k-steps of 16: K <= 384
-constexpr int kDecodeWideCols = 128;
 
-template <typename X, typename OutT, int NTB>
+template <typename X, typename OutT, int NTB, int CW>
 __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    static_assert(CW == 128 || CW == 64, "slice width");
     constexpr int CH = 6;                                 // k-steps per chunk (four chunks)
+    constexpr int WC = CW / 32, WT = 4 / WC, TPW = NTB / WT;
+    static_assert(NTB % WT == 0, "token blocks per wave");
+    constexpr int ROW_B = 2 * CW;                         // bytes of a row of the slice
+    constexpr int RPI = 1024 / ROW_B;                     // rows per request: 4 or 8
+    constexpr int KSPR = 4 * RPI / 16;                    // k-steps per round of four requests (one per wave): 1 or 2
+    constexpr int RPC = CH / KSPR;                        // requests per wave and chunk: 6 or 3
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wc = wave % WC, wt = wave / WC;
     const int l31 = lane & 31, lhi = lane >> 5;
 
     const DecodeArgs p = decode_args(p_in);
     const int slice = p.slice;
     if (slice >= p.n_tiles) return;
     const SliceGroup sg = p.sg;
-    const int rel0 = (slice - sg.tile0) * kDecodeWideCols;
+    const int rel0 = (slice - sg.tile0) * CW;
     const int64_t n0 = sg.col0 + rel0;
     const int64_t left = sg.col1 - n0;
-    const int cols_left = (int)(left > kDecodeWideCols ? kDecodeWideCols : left);
+    const int cols_left = (int)(left > CW ? CW : left);
     const int a_off = sg.a_off;
     const int T = (int)p.M;
     const int nks = (p.K + 15) >> 4;                     // <= kDecodeWideMaxKS (host contract)
     const int n_tb = (T + 31) >> 5;                      // <= NTB (host contract)
-    const int issued = (nks + 1) & ~1;                   // requests per wave for C: one per k-step, a filler for an odd count
+    const int issued = (nks + KSPR - 1) / KSPR;          // requests per wave for C
 
-    // ---- the slice of C: wave w requests rows 16 ks + 4 w .. + 3 of every k-step, in k order; the
-    // first chunk's requests go out before anything else, the rest behind the token rows -------------
+    // ---- the slice of C: request j of wave w brings rows 4 RPI j + RPI w .. + RPI - 1 to LDS offset
+    // 4096 j + 1024 w; the first chunk's requests go out before anything else, the rest behind the
+    // token rows ---------------------------------------------------------------------------------------
     const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
     const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
     uint32_t c_lane_off;
     {
-        const int r = lane >> 4;                                      // row within the instruction = row & 3
-        const int piece = (lane & 15) ^ (4 * r);                      // global piece held at LDS position lane & 15
-        c_lane_off = piece * 8 < cols_left ? (uint32_t)(4 * wave + r) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
+        constexpr int PPR = ROW_B / 16;                               // pieces per row: 16 or 8
+        const int r = lane / PPR;                                     // row within the request
+        const int swz = CW == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1);
+        const int piece = (lane % PPR) ^ swz;                         // global piece held at LDS position lane % PPR
+        c_lane_off = piece * 8 < cols_left ? (uint32_t)(RPI * wave + r) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
     }
     const uint32_t c_lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u;
-    auto request_c = [&](auto first, auto last) {                     // k-steps [first, last), two at a time
+    auto request_c = [&](auto first, auto last) {                     // requests [first, last) of this wave
 #pragma unroll
-        for (int ks = decltype(first)::value; ks < decltype(last)::value; ks += 2) {   // rows past K fall outside rB's range -> zeros
-            if (ks < nks) {
-                const uint32_t v0 = c_lane_off + (uint32_t)(ks * 16) * row_bytes;
-                const uint32_t v1 = ks + 1 < nks ? c_lane_off + (uint32_t)((ks + 1) * 16) * row_bytes : kBadOffset;
-                lds_dma1(rB, c_lds0 + (uint32_t)ks * 4096u, v0);
-                lds_dma1(rB, c_lds0 + (uint32_t)(ks + 1) * 4096u, v1);
-            }
-        }
+        for (int j = decltype(first)::value; j < decltype(last)::value; ++j)   // rows past K fall outside rB's range -> zeros
+            if (j < issued)
+                lds_dma1(rB, c_lds0 + (uint32_t)j * 4096u, c_lane_off + (uint32_t)(j * 4 * RPI) * row_bytes);
     };
-    request_c(std::integral_constant<int, 0>{}, std::integral_constant<int, CH>{});
+    request_c(std::integral_constant<int, 0>{}, std::integral_constant<int, RPC>{});
 
     // ---- the token rows: [64-k stage][token][128 bytes] behind the slice of C, piece q of a row at
     // position q ^ tok_swz<64>(row); one request = 8 rows x 128 bytes, the waves take turns -----------
@@ -386,81 +392,83 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in
                      row < T && k < p.K ? (uint32_t)row * (uint32_t)(p.lda * 2) + (uint32_t)col * 2u : kBadOffset);
         }
     }
-    request_c(std::integral_constant<int, CH>{}, std::integral_constant<int, kDecodeWideMaxKS>{});
+    request_c(std::integral_constant<int, RPC>{}, std::integral_constant<int, kDecodeWideMaxKS / KSPR>{});
 
-    // ---- identity values of this lane's results (token l31 of block tb, columns 32 wave + 8 q + 4 lhi
-    // + 0..3), wanted only in the epilogue: requested last --------------------------------------------
+    // ---- identity values of this lane's results (token l31 of the wave's block tbl, columns
+    // 32 wc + 8 q + 4 lhi + 0..3), wanted only in the epilogue: requested last ------------------------
     const __amdgpu_buffer_rsrc_t rI = make_rsrc(p.A, ((int64_t)(T - 1) * p.lda + p.K + p.a_skip) * 2);
-    u32x2 idv[NTB][4];
+    u32x2 idv[TPW][4];
 #pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
+    for (int tbl = 0; tbl < TPW; ++tbl)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int col = 32 * wave + 8 * q + 4 * lhi;
+            const int col = 32 * wc + 8 * q + 4 * lhi;
             if (p.ident) {
                 const int j = (rel0 + col) % p.d_h;
-                idv[tb][q] = __builtin_amdgcn_raw_buffer_load_b64(
-                    rI, col < cols_left ? (uint32_t)(tb * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
-            } else idv[tb][q] = (u32x2){0u, 0u};
+                idv[tbl][q] = __builtin_amdgcn_raw_buffer_load_b64(
+                    rI, col < cols_left ? (uint32_t)((wt * TPW + tbl) * 32 + l31) * (uint32_t)(p.lda * 2) + (uint32_t)(a_off + j) * 2u : kBadOffset, 0, 0);
+            } else idv[tbl][q] = (u32x2){0u, 0u};
         }
-    const int n_idv = p.ident ? 4 * NTB : 0;
+    const int n_idv = p.ident ? 4 * TPW : 0;
 
-    f32x16 acc[NTB];
+    f32x16 acc[TPW];
 #pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
+    for (int tbl = 0; tbl < TPW; ++tbl)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[tb][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc[tbl][r] = 0.0f;
 
     // transposing-read address: 16-lane group gq, s = lane % 16: row 8 lhi + s / 4 (+ 4 for the second
-    // read), columns 32 wave + 16 (gq & 1) + 4 (s & 3) .. + 3
+    // read), columns 32 wc + 16 (gq & 1) + 4 (s & 3) .. + 3
     const int c_s = lane & 15, c_gq = lane >> 4;
-    const int w_col = 32 * wave + 16 * (c_gq & 1) + 4 * (c_s & 3);
-    const uint32_t w_rd = (uint32_t)((8 * lhi + (c_s >> 2)) * 256 + (((w_col >> 3) ^ (4 * (c_s >> 2))) << 4) + ((w_col & 4) << 1));
+    const int w_col = 32 * wc + 16 * (c_gq & 1) + 4 * (c_s & 3);
+    const int w_swz = CW == 128 ? 4 * (c_s >> 2) : 4 * ((c_s >> 3) & 1);
+    const uint32_t w_rd = (uint32_t)((8 * lhi + (c_s >> 2)) * ROW_B + (((w_col >> 3) ^ w_swz) << 4) + ((w_col & 4) << 1));
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
 
     // fragment read of token block tb, k-step ks: row 32 tb + l31, pieces 2 (ks & 3) + lhi of stage ks / 4
     typedef __attribute__((address_space(3))) const u32x4* lds_u32x4;
     const uint32_t t_rd = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + tok_lds
-                          + (uint32_t)(l31 * 128 + ((lhi ^ tok_swz<64>(l31 & 15)) << 4));
+                          + (uint32_t)(wt * TPW * 4096 + l31 * 128 + ((lhi ^ tok_swz<64>(l31 & 15)) << 4));
 
     // ---- four chunks of six k-steps: wait for this wave's requests of the chunk, meet the others ---
     // (the counter is in order: the token requests follow the first chunk's, so whatever may still
     // fly at chunk c are the requests for C of later chunks and the identity values)
 #pragma unroll
     for (int c = 0; c < kDecodeWideMaxKS / CH; ++c) {
-        const int later = issued - CH * (c + 1);
+        const int later = issued - RPC * (c + 1);
         wait_vmcnt_at_most((later > 0 ? later : 0) + n_idv);
         __syncthreads();
         const int ks_end = nks < CH * (c + 1) ? nks : CH * (c + 1);
         for (int ks = CH * c; ks < ks_end; ++ks) {       // (a plain loop: the accumulators stay where they are)
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 4096));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * 4096 + 1024));
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * (16 * ROW_B)));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * (16 * ROW_B) + 4 * ROW_B));
             const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
             const u32x4 fw = {lo2[0], lo2[1], hi2[0], hi2[1]};
             const uint32_t ta = (t_rd + (uint32_t)((ks >> 2) * (NTB * 4096))) ^ (uint32_t)((ks & 3) << 5);
 #pragma unroll
-            for (int tb = 0; tb < NTB; ++tb)               // (blocks past T hold zeros)
-                acc[tb] = X::mfma(fw, *(lds_u32x4)(uintptr_t)(ta + tb * 4096), acc[tb]);
+            for (int tbl = 0; tbl < TPW; ++tbl)            // (blocks past T hold zeros)
+                acc[tbl] = X::mfma(fw, *(lds_u32x4)(uintptr_t)(ta + tbl * 4096), acc[tbl]);
         }
     }
 
-    // ---- epilogue: lane (token l31, half lhi) holds columns 32 wave + 8 q + 4 lhi + 0..3, q = 0..3 ---
+    // ---- epilogue: lane (token l31, half lhi) holds columns 32 wc + 8 q + 4 lhi + 0..3, q = 0..3 -----
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
                                                 ((int64_t)(T - 1) * p.ldd + cols_left) * (int64_t)sizeof(OutT));
 #pragma unroll
-    for (int tb = 0; tb < NTB; ++tb) {
+    for (int tbl = 0; tbl < TPW; ++tbl) {
+        const int tb = wt * TPW + tbl;
         if (tb >= n_tb) break;
         const int t = tb * 32 + l31;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int col = 32 * wave + 8 * q + 4 * lhi;
-            float v[4] = {acc[tb][4 * q], acc[tb][4 * q + 1], acc[tb][4 * q + 2], acc[tb][4 * q + 3]};
+            const int col = 32 * wc + 8 * q + 4 * lhi;
+            float v[4] = {acc[tbl][4 * q], acc[tbl][4 * q + 1], acc[tbl][4 * q + 2], acc[tbl][4 * q + 3]};
             if (p.ident) {
-                v[0] += X::to_f32((uint16_t)(idv[tb][q][0] & 0xffffu));
-                v[1] += X::to_f32((uint16_t)(idv[tb][q][0] >> 16));
-                v[2] += X::to_f32((uint16_t)(idv[tb][q][1] & 0xffffu));
-                v[3] += X::to_f32((uint16_t)(idv[tb][q][1] >> 16));
+                v[0] += X::to_f32((uint16_t)(idv[tbl][q][0] & 0xffffu));
+                v[1] += X::to_f32((uint16_t)(idv[tbl][q][0] >> 16));
+                v[2] += X::to_f32((uint16_t)(idv[tbl][q][1] & 0xffffu));
+                v[3] += X::to_f32((uint16_t)(idv[tbl][q][1] >> 16));
             }
             const uint32_t off = col < cols_left ? (uint32_t)t * (uint32_t)(p.ldd * sizeof(OutT)) + (uint32_t)col * (uint32_t)sizeof(OutT) : kBadOffset;
             if constexpr (sizeof(OutT) == 4) {

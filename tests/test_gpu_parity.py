@@ -63,6 +63,25 @@ def test_config3_decode_shapes_wide_slices(T):
     _run_kv_case(w, [0, 0], policy=5)
 
 
+@pytest.mark.parametrize("T", [65, 100, 128])
+@pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.BF16, wl.F32)])
+def test_decode_64_column_slices(T, dtype, out_dtype):
+    """65 .. 128 tokens through the 64-column variant of the wide-slice kernel (policy 5; automatic
+    where 32-column slices would outnumber the compute units): windows off the 64 grid, a group that
+    ends inside a slice, the contraction at the limit 384 and a short one."""
+    w = wl.custom_kv_workload("dec64_a", T=T, d_c=512, d_h=128, H=[3, 2], std=0.02, rms_norm=True, dtype=dtype, seed=60 + T)
+    _run_kv_case(w, [72, 384], out_dtype=out_dtype, policy=5)
+    w = wl.custom_kv_workload("dec64_b", T=T, d_c=96, d_h=40, H=[1, 2], std=0.1, rms_norm=True, dtype=dtype, seed=61 + T)
+    _run_kv_case(w, [56, 0], out_dtype=out_dtype, policy=5)
+    w = wl.custom_kv_workload("dec64_c", T=T, d_c=440, d_h=56, H=[5, 1], std=0.05, rms_norm=True, dtype=dtype, seed=62 + T)
+    _run_kv_case(w, [0, 384], out_dtype=out_dtype, policy=5)
+    if dtype == wl.BF16 and out_dtype is None:           # automatic choice: 72 heads = 9216 columns = 288 / 144 slices
+        w = wl.custom_kv_workload("dec64_auto", T=T, d_c=512, d_h=128, H=[40, 32], std=0.02, rms_norm=True, dtype=dtype, seed=63 + T)
+        p = bda.bda_kv_project_plan(T, 512, 128, [40, 32], [0, 200], dtype)
+        assert (p["kernel"], p["tile_tokens"], p["tile_columns"], p["workgroups"]) == (bda.KERNEL_DECODE, 128, 64, 144)
+        _run_kv_case(w, [0, 200])
+
+
 @pytest.mark.parametrize("T", [1, 31, 64])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, wl.F32)])
 def test_decode_wide_slices_automatic(T, dtype, out_dtype):

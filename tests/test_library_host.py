@@ -229,7 +229,10 @@ def test_launch_plan_benchmark_shapes():
     for T in (65, 128):                                                 # up to 128 tokens while every slice has a CU
         p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
         assert (p["kernel"], p["tile_tokens"], p["tile_columns"], p["workgroups"]) == (bda.KERNEL_DECODE, 128, 32, 128)
-        assert _plan(T, [40, 40], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_LEAN      # 320 slices: tiles
+        p = _plan(T, [40, 40], [0, 0], bda.BDA_F16)                     # 320 slices of 32: 160 slices of 64 instead
+        assert (p["kernel"], p["tile_columns"], p["workgroups"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 64, 160, 144 * 1024)
+        assert _plan(T, [96, 96], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_LEAN      # 384 slices of 64: tiles
+        assert _plan(T, [40, 40], [0, 0], bda.BDA_F16, d_c=1024)["kernel"] == bda.KERNEL_LEAN   # K = 896 > 384
     p = _plan(64, [128, 128], [0, 0], bda.BDA_BF16)                     # wide output: 128-column slices
     assert (p["kernel"], p["tile_columns"], p["workgroups"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 128, 256, 144 * 1024)
     p = _plan(16, [128, 128], [0, 0], bda.BDA_BF16)
