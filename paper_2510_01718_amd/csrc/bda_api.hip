@@ -236,12 +236,13 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     for (int g = 0; g < G; ++g) fast = fast && a.a_off[g] % 8 == 0 && group_cols[g] % 8 == 0;
 
     // Small-T kernels (policy 5 forces the wide-slice one wherever it applies and otherwise acts as 0).
-    // Measured on cold weights, K = 384: with 32-column slices the time grows with the number of
-    // workgroups per compute unit, so beyond about 20 k columns one workgroup per 128 columns wins
-    // (N = 32768: 9.5-12 us against 12.5-17 us), below it loses to the finer split (N = 4096:
-    // 6.7-8.6 against 5.3-6.0); for 65 .. 128 tokens the 32-column kernel with four token blocks
-    // beats 128-token tiles while every slice has a compute unit of its own (N = 4096: 6.6-8.0 us
-    // against 10.6) and loses beyond.
+    // Measured on cold weights, K = 384, us.  Up to 64 tokens: with 32-column slices the time grows
+    // with the number of workgroups per compute unit, so beyond about 20 k columns one workgroup per
+    // 128 columns wins (N = 32768: 9.1-10.4 against 12.5-17), below it loses to the finer split
+    // (N = 4096: 6.4-7.4 against 4.0-5.4).  65 .. 128 tokens: the 32-column kernel with four token
+    // blocks while every slice has a compute unit of its own (N = 4096: 5.8-7.3 against 10.6 with
+    // 128-token tiles), then 64-column slices while those have (N = 12288 .. 16384: 8.4-9.4 against
+    // 10.7-11.0), the tiles beyond (N = 24576: 11.3 against 15-16).
     const int policy0 = g_tile_policy.load();
     const bool small_policy = policy0 == 0 || policy0 == 5;
     int64_t n_slices128 = 0, n_slices64 = 0, n_slices32 = 0;
@@ -250,8 +251,6 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         n_slices64 += (group_cols[g] + 63) / 64;
         n_slices32 += (group_cols[g] + 31) / 32;
     }
-    // (65 .. 128 tokens: the 64-column slices where the 32-column ones would not have a compute unit each but these
-    // do: N = 12288 .. 16384 takes 8.4-9.4 us against 10.7-11.0 with 128-token tiles; wider outputs are left to the tiles)
     const bool wide_auto = a.M <= 64 ? n_slices128 >= 160 : (n_slices32 > 256 && n_slices64 <= 256);
     if (fast && ident_vec && a.M <= kDecodeMaxT && a.K <= 16 * kDecodeWideMaxKS && (policy0 == 5 || (policy0 == 0 && wide_auto))) {
         // a few tokens, wide output: stream the weights once, 128 (64) output columns per workgroup
