@@ -233,6 +233,35 @@ def test_kv_strided_buffers_and_untouched_padding():
         assert np.all(pad == np.float16(-7.0)), "columns beyond N were written"
 
 
+@pytest.mark.parametrize("T", [8, 50, 100])
+@pytest.mark.parametrize("policy", [0, 5])
+def test_small_T_kernels_strided_buffers_and_exact_copy(T, policy):
+    """The small-T kernels (32-column slices at policy 0, 128- or 64-column slices at policy 5) with
+    row pitches larger than the rows: results as with dense buffers, padding untouched; and with
+    C = 0 the output is the basis slice bit for bit (float32 identity add, one rounding)."""
+    w = wl.custom_kv_workload("strided_small", T=T, d_c=512, d_h=128, H=[2, 1], std=0.02, rms_norm=True,
+                              dtype=wl.F16, seed=18 + T)
+    offs = [8, 384]
+    C_stored, C64 = _prepare_stored(w.W, w.d_c, w.H, w.d_h, offs, w.dtype)
+    ref = oracle.kv_project(w.c, C64, w.d_h, w.H, offs)
+    N = w.N
+    bda.bda_set_tile_policy(policy)
+    try:
+        assert bda.bda_kv_project_plan(T, 512, 128, w.H, offs, w.dtype, ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24)["kernel"] == bda.KERNEL_DECODE
+        got, raw = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype,
+                                 ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24, fill=-7.0)
+        zero_C, _ = wl.to_storage(np.zeros((384, N)), w.dtype)
+        copy, _ = gh.kv_project(w.c_stored, zero_C, w.d_c, w.d_h, w.H, offs, w.dtype)
+    finally:
+        bda.bda_set_tile_policy(0)
+    assert_parity(got, ref, w.d_h, w.dtype, w.dtype, "strided small T")
+    pad = raw[:, N:].cpu().numpy()
+    assert np.all(pad == np.float16(-7.0)), "columns beyond N were written"
+    for h in range(3):
+        off = offs[0] if h < 2 else offs[1]
+        assert np.array_equal(copy[:, h * 128:(h + 1) * 128], w.c[:, off:off + 128]), (h, policy)
+
+
 def test_kv_general_kernel_for_unaligned_shapes():
     # d_h = 20 and d_c = 52 satisfy none of the MFMA path's alignment rules
     w = wl.custom_kv_workload("unaligned", T=77, d_c=52, d_h=20, H=[2, 3], std=0.1, rms_norm=False,
