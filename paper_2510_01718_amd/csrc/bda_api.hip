@@ -128,9 +128,9 @@ int launch_decode_blocks(GemmArgs& a, hipStream_t st)
     auto kern = kv_decode_kernel<X, OutT, NTB, TOK_LDS>;
     const int lds = decode_lds_bytes<NTB, TOK_LDS>(a.K);
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
-    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, 32, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
+    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, 32, kNumXcd * per_xcd * a.m_tiles, 256, lds, 1)) return BDA_OK;
     if (int rc = set_max_lds(kern, decode_lds_bytes<NTB, TOK_LDS>(TOK_LDS ? kDecodeTokLdsMaxK : kDecodeMaxK), once)) return rc;
-    hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd * a.m_tiles), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
@@ -144,9 +144,9 @@ int launch_decode_wide_blocks(GemmArgs& a, hipStream_t st)
     const int nks = (a.K + 15) / 16;
     const int lds = ((nks + kspr - 1) / kspr) * 4096 + ((a.K + 63) / 64) * NTB * 4096;   // slice of C, token rows
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
-    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, CW, kNumXcd * per_xcd, 256, lds, 1)) return BDA_OK;
+    if (plan_only(a, BDA_KERNEL_DECODE, 32 * NTB, CW, kNumXcd * per_xcd * a.m_tiles, 256, lds, 1)) return BDA_OK;
     if (int rc = set_max_lds(kern, (kDecodeWideMaxKS / kspr) * 4096 + (kDecodeWideMaxKS / 4) * NTB * 4096, once)) return rc;
-    hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd), dim3(256), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(kNumXcd * per_xcd * a.m_tiles), dim3(256), lds, st, a);
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
@@ -251,19 +251,24 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         n_slices64 += (group_cols[g] + 63) / 64;
         n_slices32 += (group_cols[g] + 31) / 32;
     }
-    const bool wide_auto = a.M <= 64 ? n_slices128 >= 160 : (n_slices32 > 256 && n_slices64 <= 256);
-    if (fast && ident_vec && a.M <= kDecodeMaxT && a.K <= 16 * kDecodeWideMaxKS && (policy0 == 5 || (policy0 == 0 && wide_auto))) {
+    // More than 128 tokens are cut into token tiles of 128 while all the workgroups still fit the chip at once
+    // (T = 256, N = 4096: 256 workgroups).
+    const int64_t tok_tiles = (a.M + kDecodeMaxT - 1) / kDecodeMaxT;
+    const bool fits32 = n_slices32 * tok_tiles <= 256, fits64 = n_slices64 * tok_tiles <= 256;
+    const bool wide_auto = a.M <= 64 ? n_slices128 >= 160 : (!fits32 && fits64);
+    const bool small_T = a.M <= 64 || (a.M <= kDecodeMaxT * 8 && (fits32 || fits64 || (policy0 == 5 && a.M <= kDecodeMaxT)));
+    if (fast && ident_vec && small_T && a.K <= 16 * kDecodeWideMaxKS && (policy0 == 5 || (policy0 == 0 && wide_auto))) {
         // a few tokens, wide output: stream the weights once, 128 (64) output columns per workgroup
-        build_tiles(a, G, group_cols, kDecodeMaxT, a.M <= 64 ? 128 : 64);
+        build_tiles(a, G, group_cols, a.M <= 64 ? 64 : kDecodeMaxT, a.M <= 64 ? 128 : 64);
         a.sm = a.sn = 1;
         if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_decode_wide<F16, uint16_t>(a, st);
         if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_decode_wide<F16, float>(a, st);
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_decode_wide<BF16, uint16_t>(a, st);
         if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_decode_wide<BF16, float>(a, st);
     }
-    if (fast && ident_vec && small_policy && a.M <= kDecodeMaxT && a.K <= kDecodeMaxK && (a.M <= 64 || n_slices32 <= 256)) {
+    if (fast && ident_vec && small_policy && a.K <= kDecodeMaxK && (a.M <= 64 || (a.M <= kDecodeMaxT * 8 && fits32))) {
         // a few tokens: stream the weights once, 32 output columns per workgroup
-        build_tiles(a, G, group_cols, kDecodeMaxT, 32);
+        build_tiles(a, G, group_cols, a.M <= 64 ? 64 : kDecodeMaxT, 32);
         a.sm = a.sn = 1;
         if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_decode<F16, uint16_t>(a, st);
         if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_decode<F16, float>(a, st);

@@ -78,12 +78,22 @@ struct DecodeArgs {
     int K, d_h, a_skip, ident, n_tiles, slice;
     SliceGroup sg;
 };
-__device__ __forceinline__ DecodeArgs decode_args(const GemmArgs& p)
+// More tokens than a workgroup takes (ROWS) are cut into token tiles: the grid is m_tiles copies of
+// the slice grid, and a workgroup sees its tile as a problem of its own (A, D and M are those of
+// the tile), so the kernels below never know.
+template <int ROWS>
+__device__ __forceinline__ DecodeArgs decode_args(const GemmArgs& p, int out_elem_bytes)
 {
     DecodeArgs q = {p.A, p.B, p.D, p.lda, p.ldb, p.ldd, p.M, p.K, p.d_h, p.a_skip, p.ident, p.n_tiles, 0, {0, 0, 0, 0}};
     // dies take contiguous runs of slices
     const int per_xcd = (q.n_tiles + kNumXcd - 1) / kNumXcd;
-    q.slice = (int)(blockIdx.x % kNumXcd) * per_xcd + (int)(blockIdx.x / kNumXcd);
+    const int idx = (int)(blockIdx.x / kNumXcd);
+    const int ttile = p.m_tiles > 1 ? idx / per_xcd : 0;
+    q.slice = (int)(blockIdx.x % kNumXcd) * per_xcd + idx - ttile * per_xcd;
+    const int64_t t0 = (int64_t)ttile * ROWS;
+    q.A = (const char*)q.A + t0 * q.lda * 2;
+    q.D = (char*)q.D + t0 * q.ldd * out_elem_bytes;
+    q.M = q.M - t0 < ROWS ? q.M - t0 : ROWS;
     q.sg = slice_group(p, q.slice);
     asm volatile("" : "+s"(q.A), "+s"(q.B), "+s"(q.D), "+s"(q.lda), "+s"(q.ldb), "+s"(q.ldd), "+s"(q.M),
                  "+s"(q.sg.col0), "+s"(q.sg.col1));
@@ -108,7 +118,7 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
     const int l31 = lane & 31, lhi = lane >> 5;
 
     // slice owned by this workgroup
-    const DecodeArgs p = decode_args(p_in);
+    const DecodeArgs p = decode_args<32 * NTB>(p_in, (int)sizeof(OutT));
     const int slice = p.slice;
     if (slice >= p.n_tiles) return;
     const SliceGroup sg = p.sg;
@@ -339,7 +349,7 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in
     const int wc = wave % WC, wt = wave / WC;
     const int l31 = lane & 31, lhi = lane >> 5;
 
-    const DecodeArgs p = decode_args(p_in);
+    const DecodeArgs p = decode_args<32 * NTB>(p_in, (int)sizeof(OutT));
     const int slice = p.slice;
     if (slice >= p.n_tiles) return;
     const SliceGroup sg = p.sg;

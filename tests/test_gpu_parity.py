@@ -82,6 +82,23 @@ def test_decode_64_column_slices(T, dtype, out_dtype):
         _run_kv_case(w, [0, 200])
 
 
+@pytest.mark.parametrize("T", [129, 200, 256, 300, 700])
+@pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, wl.F32)])
+def test_small_T_kernels_with_token_tiles(T, dtype, out_dtype):
+    """More than 128 tokens through the small-T kernels: token tiles of 128 (the last one ragged) while
+    slices x token tiles <= 256.  640 columns: 32-column slices (20 x 2 .. 6 token tiles); 8192
+    columns at up to 256 tokens: 64-column slices (128 x 2)."""
+    w = wl.custom_kv_workload("tiles32", T=T, d_c=512, d_h=128, H=[3, 2], std=0.02, rms_norm=True, dtype=dtype, seed=70 + T)
+    p = bda.bda_kv_project_plan(T, 512, 128, [3, 2], [72, 384], dtype, out_dtype=out_dtype)
+    assert (p["kernel"], p["tile_columns"], p["token_tiles"]) == (bda.KERNEL_DECODE, 32, (T + 127) // 128)
+    _run_kv_case(w, [72, 384], out_dtype=out_dtype)
+    if T <= 256:
+        w = wl.custom_kv_workload("tiles64", T=T, d_c=512, d_h=128, H=[34, 30], std=0.02, rms_norm=True, dtype=dtype, seed=71 + T)
+        p = bda.bda_kv_project_plan(T, 512, 128, [34, 30], [0, 200], dtype, out_dtype=out_dtype)
+        assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 64, 2, 256)
+        _run_kv_case(w, [0, 200], out_dtype=out_dtype)
+
+
 @pytest.mark.parametrize("T", [1, 31, 64])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, wl.F32)])
 def test_decode_wide_slices_automatic(T, dtype, out_dtype):
@@ -169,12 +186,14 @@ def test_kv_lean_head_widths(policy, d_c, d_h, H, offs):
     _run_kv_case(w, offs, policy=policy)
 
 
-@pytest.mark.parametrize("T", [100, 1300, 1536])
+@pytest.mark.parametrize("T", [600, 1300, 1536])
 def test_kv_lean_automatic_tile_choice(T):
     """Automatic policy on the V2-Lite shape at token counts that select 128-token tiles
     (tile-by-tile order at 1536: 12 x 16 tiles)."""
     w = wl.custom_kv_workload("auto", T=T, d_c=512, d_h=128, H=[16, 16], std=0.02, rms_norm=True,
                               dtype=wl.F16, seed=23)
+    p = bda.bda_kv_project_plan(T, 512, 128, [16, 16], [0, 0], wl.F16)
+    assert (p["kernel"], p["tile_tokens"]) == (bda.KERNEL_LEAN, 128)
     _run_kv_case(w, [0, 0])
 
 

@@ -233,6 +233,12 @@ def test_launch_plan_benchmark_shapes():
         assert (p["kernel"], p["tile_columns"], p["workgroups"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 64, 160, 144 * 1024)
         assert _plan(T, [96, 96], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_LEAN      # 384 slices of 64: tiles
         assert _plan(T, [40, 40], [0, 0], bda.BDA_F16, d_c=1024)["kernel"] == bda.KERNEL_LEAN   # K = 896 > 384
+    # more than 128 tokens: token tiles of 128 while all the workgroups fit the chip at once
+    p = _plan(256, [16, 16], [0, 0], bda.BDA_F16)
+    assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 32, 2, 256)
+    p = _plan(512, [16, 16], [0, 0], bda.BDA_F16)
+    assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 64, 4, 256)
+    assert _plan(600, [16, 16], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_LEAN
     p = _plan(64, [128, 128], [0, 0], bda.BDA_BF16)                     # wide output: 128-column slices
     assert (p["kernel"], p["tile_columns"], p["workgroups"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 128, 256, 144 * 1024)
     p = _plan(16, [128, 128], [0, 0], bda.BDA_BF16)
@@ -249,7 +255,7 @@ def test_launch_plan_benchmark_shapes():
 def test_launch_plan_tile_choice_by_rounds():
     """128-token tiles where they need fewer than 1/0.56 times the rounds of 256-token tiles; dies
     take single tiles where whole super-tiles would need more rounds."""
-    want = {200: (128, 1, 0), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
+    want = {600: (128, 1, 0), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
             3072: (256, 1, 1), 4096: (256, 1, 0), 5120: (128, 3, 0), 8192: (256, 2, 0)}
     for T, (tokens, rounds, by_tile) in want.items():
         p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
@@ -276,7 +282,8 @@ def test_launch_plan_preconditions_of_the_lean_kernel():
     # window start not a multiple of 8, row pitch not a multiple of 8, head width not a multiple of 32
     assert _plan(4096, [16, 16], [4, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_GENERAL
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, ldc=516)["kernel"] == bda.KERNEL_GENERAL
-    assert _plan(300, [4], [0], bda.BDA_F16, d_c=96, d_h=24)["kernel"] == bda.KERNEL_GENERAL
+    assert _plan(1100, [4], [0], bda.BDA_F16, d_c=96, d_h=24)["kernel"] == bda.KERNEL_GENERAL
+    assert _plan(300, [4], [0], bda.BDA_F16, d_c=96, d_h=24)["kernel"] == bda.KERNEL_DECODE   # (few tokens: head width % 8 is enough)
     # the tile policy hook
     try:
         bda.bda_set_tile_policy(1)
