@@ -198,7 +198,7 @@ int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64
  * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256,
  * 3 = 256 x 256 with the general streaming kernel even where its lean variant would apply,
  * 4 = 128 x 256 with the lean streaming kernel where it applies (else as 2),
- * 5 = automatic, except that up to 128 tokens take the wide-slice small-T kernel (128 columns per
+ * 5 = automatic, except that up to 128 tokens always take the wide-slice small-T kernel (128 columns per
  * workgroup up to 64 tokens, 64 columns above) wherever it applies (contraction d_c - d_h <= 384),
  * whatever the output width.
  * bda_kv_project_backward honours 1 (128 x 128 output tiles) and treats the rest as automatic.
@@ -219,7 +219,7 @@ typedef enum {
     BDA_KERNEL_MFMA = 2,    /* register-staged MFMA kernel, 128 x 128 or 256 x 256 tiles */
     BDA_KERNEL_STREAM = 3,  /* streaming MFMA kernel (LDS DMA ring), general variant */
     BDA_KERNEL_LEAN = 4,    /* streaming MFMA kernel, lean variant (256- or 128-token tiles) */
-    BDA_KERNEL_DECODE = 5   /* T <= 128: weight-streaming kernels; tile_columns tells 32-, 64- and 128-column slices apart */
+    BDA_KERNEL_DECODE = 5   /* few tokens (token tiles of up to 128): weight-streaming kernels; tile_columns tells 32-, 64- and 128-column slices apart */
 } bda_kernel_id;
 
 typedef struct {
