@@ -363,11 +363,11 @@ def test_dense_project(dtype, policy):
     assert_parity(gh.to_host64(out_d, dtype), ref, 128, dtype, dtype, "dense")
 
 
-@pytest.mark.parametrize("T", [1, 40, 64, 100])
+@pytest.mark.parametrize("T", [1, 40, 64, 100, 300])
 @pytest.mark.parametrize("policy", [0, 5])
 def test_dense_project_few_tokens(T, policy):
     """The small-T kernels without an identity slice: 32-column slices (policy 0; four token blocks
-    at T = 100) and 128-column slices (policy 5, up to 64 tokens), contraction 320."""
+    at T = 100, three token tiles at T = 300) and 128- / 64-column slices (policy 5), contraction 320."""
     dtype = wl.BF16
     w = wl.custom_kv_workload("dense_few", T=T, d_c=320, d_h=64, H=[9], std=0.05, rms_norm=True, dtype=dtype, seed=23 + T)
     W_stored, W64 = wl.to_storage(w.W, dtype)
