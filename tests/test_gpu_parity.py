@@ -99,6 +99,40 @@ def test_small_T_kernels_with_token_tiles(T, dtype, out_dtype):
         _run_kv_case(w, [0, 200], out_dtype=out_dtype)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_small_T_kernels_random_shapes(seed):
+    """Seeded random small problems (1 .. 500 tokens, head widths 8 .. 128, contraction 8 .. 384, one to
+    three groups with windows anywhere on the multiples of 8, padded row pitches) through the
+    automatic choice and through policy 5, against the oracle on the same stored numbers; columns
+    past N stay untouched."""
+    rng = np.random.default_rng(1000 + seed)
+    for case in range(40):
+        d_h = int(rng.choice([8, 16, 24, 32, 40, 56, 64, 96, 128]))
+        K = 8 * int(rng.integers(1, 49))
+        d_c = K + d_h
+        G = int(rng.integers(1, 4))
+        H = [int(rng.integers(1, 6)) for _ in range(G)]
+        offs = [8 * int(rng.integers(0, K // 8 + 1)) for _ in range(G)]
+        T = int(rng.choice([1, 2, 7, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 200, 256, 257, 300, 500]))
+        N = sum(H) * d_h
+        dtype = wl.F16 if rng.integers(0, 2) else wl.BF16
+        ldc, ldC, ld_out = (v + 8 * int(rng.integers(0, 3)) for v in (d_c, N, N))
+        c_stored, c64 = wl.to_storage(rng.standard_normal((T, d_c)), dtype)
+        C_stored, C64 = wl.to_storage(rng.standard_normal((K, N)) * 0.2, dtype)
+        ref = oracle.kv_project(c64, C64, d_h, H, offs)
+        for policy in (0, 5):
+            what = f"seed {seed} case {case} policy {policy}: T={T} d_c={d_c} d_h={d_h} H={H} offs={offs} ld=({ldc},{ldC},{ld_out})"
+            bda.bda_set_tile_policy(policy)
+            try:
+                got, raw = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0)
+            finally:
+                bda.bda_set_tile_policy(0)
+            assert_parity(got, ref, d_h, dtype, dtype, what)
+            if ld_out > N:
+                pad = raw[:, N:].cpu().numpy()
+                assert np.all(pad == (np.float16(-7.0) if dtype == wl.F16 else -7)), what + ": columns beyond N were written"
+
+
 @pytest.mark.parametrize("T", [1, 31, 64])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, wl.F32)])
 def test_decode_wide_slices_automatic(T, dtype, out_dtype):
