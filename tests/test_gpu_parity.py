@@ -133,6 +133,37 @@ def test_small_T_kernels_random_shapes(seed):
                 assert np.all(pad == (np.float16(-7.0) if dtype == wl.F16 else -7)), what + ": columns beyond N were written"
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_tile_kernels_random_shapes(seed):
+    """Seeded random mid-size problems (129 .. 2049 tokens, head widths 32 .. 256, contraction on and off
+    the multiples of 64, groups that do and do not fill 256-column tiles, windows anywhere on the
+    multiples of 8, padded row pitches) through every tile policy, against the oracle."""
+    rng = np.random.default_rng(2000 + seed)
+    for case in range(12):
+        d_h = int(rng.choice([32, 64, 128, 192, 256]))
+        K = 64 * int(rng.integers(1, 9)) if rng.integers(0, 4) else 8 * int(rng.integers(4, 60))
+        d_c = K + d_h
+        G = int(rng.integers(1, 4))
+        mult = max(1, 256 // d_h)
+        H = [int(rng.integers(1, 5)) * (mult if rng.integers(0, 3) else 1) for _ in range(G)]
+        offs = [8 * int(rng.integers(0, K // 8 + 1)) for _ in range(G)]
+        T = int(rng.choice([129, 255, 256, 300, 511, 640, 700, 1024, 1300, 2049]))
+        N = sum(H) * d_h
+        dtype = wl.F16 if rng.integers(0, 2) else wl.BF16
+        ldc, ldC, ld_out = (v + 8 * int(rng.integers(0, 2)) for v in (d_c, N, N))
+        c_stored, c64 = wl.to_storage(rng.standard_normal((T, d_c)), dtype)
+        C_stored, C64 = wl.to_storage(rng.standard_normal((K, N)) * 0.2, dtype)
+        ref = oracle.kv_project(c64, C64, d_h, H, offs)
+        for policy in (0, 1, 2, 3, 4, 5):
+            what = f"seed {seed} case {case} policy {policy}: T={T} d_c={d_c} d_h={d_h} H={H} offs={offs} ld=({ldc},{ldC},{ld_out})"
+            bda.bda_set_tile_policy(policy)
+            try:
+                got, _ = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0)
+            finally:
+                bda.bda_set_tile_policy(0)
+            assert_parity(got, ref, d_h, dtype, dtype, what)
+
+
 @pytest.mark.parametrize("T", [1, 31, 64])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, wl.F32)])
 def test_decode_wide_slices_automatic(T, dtype, out_dtype):
