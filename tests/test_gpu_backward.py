@@ -135,3 +135,25 @@ def test_backward_writes_nothing_outside_its_matrices():
 def test_backward_benchmark_shape_full():
     """The V2-Lite-shaped training step (T = 4096, 16 + 16 heads, fp16): every element."""
     _check(4096, 512, 128, [16, 16], [0, 0], wl.F16, what="v2lite")
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_backward_random_shapes(seed):
+    """Seeded random shapes (head widths 32 .. 128 incl. 96, contraction 32 .. 448 in steps of 8 with
+    windows anywhere on the multiples of 8, one to three groups, 1 .. 700 tokens, padded rows) through
+    both tile shapes of the gradient kernels."""
+    rng = np.random.default_rng(3000 + seed)
+    for case in range(14):
+        d_h = int(rng.choice([32, 64, 96, 128]))
+        K = 8 * int(rng.integers(4, 57))
+        d_c = K + d_h
+        G = int(rng.integers(1, 4))
+        H = [int(rng.integers(1, 5)) for _ in range(G)]
+        offs = [8 * int(rng.integers(0, K // 8 + 1)) for _ in range(G)]
+        T = int(rng.choice([1, 33, 64, 100, 129, 256, 300, 700]))
+        dtype = wl.F16 if rng.integers(0, 2) else wl.BF16
+        grad_dtype = wl.F32 if rng.integers(0, 3) == 0 else None
+        pad = 8 * int(rng.integers(0, 3))
+        for policy in (0, 1):
+            _check(T, d_c, d_h, H, offs, dtype, grad_dtype=grad_dtype, pad=pad, policy=policy, seed=seed * 100 + case,
+                   what=f"seed {seed} case {case}")
