@@ -304,6 +304,31 @@ def main() -> int:
         extra["v3_dense_T8192_bf16"] = {"us": t4d * 1e6, "tflops": 2.0 * T4 * d_c * N4 / t4d / 1e12}
         extra["v3_speedup_vs_dense"] = {"measured": t4d / t4, "theoretical": d_c / K}
         del c4, C4, o4, W4
+        # token-count sweep on the V3 k_proj shape (N = 16384, bf16; same weights every launch, as in
+        # the throughput tables of Section "BDA Inference Efficiency"): BD projection, our dense
+        # comparator, and the vendor GEMM (torch.matmul) doing the dense product
+        Ns = 128 * 128
+        Cs_ = dev(wl.to_storage(rng.standard_normal((K, Ns)) * 2.0, wl.BF16)[0], wl.BF16)
+        Ws_ = dev(wl.to_storage(rng.standard_normal((d_c, Ns)) * 0.02, wl.BF16)[0], wl.BF16)
+        sweep = {}
+        for Ts in (1, 8, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
+            cs_ = dev(wl.to_storage(rng.standard_normal((Ts, d_c)), wl.BF16)[0], wl.BF16)
+            os_ = torch.empty((Ts, Ns), dtype=torch.int16, device="cuda")
+            n_s, n_w = (max(4, min(100, args.steps // 2)), 4) if Ts <= 2048 else (max(3, min(20, args.steps // 10)), 4)
+            bd_s = lambda i, s: bda.bda_kv_project(cs_, d_c, Ts, d_c, d_h, [128], [0], Cs_, Ns, os_, Ns, wl.BF16, wl.BF16, s)
+            bench_small(bd_s, n_s, n_w)                    # untimed: clocks settle on this shape first
+            t_b = bench_small(lambda i, s: bda.bda_kv_project(cs_, d_c, Ts, d_c, d_h, [128], [0], Cs_, Ns, os_, Ns,
+                                                              wl.BF16, wl.BF16, s), n_s, n_w)
+            t_d = bench_small(lambda i, s: bda.bda_dense_project(cs_, d_c, Ts, d_c, Ws_, Ns, Ns, os_, Ns,
+                                                                 wl.BF16, wl.BF16, s), n_s, n_w)
+            cb_, Wb_, ob_ = cs_.view(torch.bfloat16), Ws_.view(torch.bfloat16), os_.view(torch.bfloat16)
+            t_v = bench_small(lambda i, s: torch.matmul(cb_, Wb_, out=ob_), n_s, n_w)
+            sweep[f"T{Ts}"] = {"bd_us": t_b * 1e6, "dense_us": t_d * 1e6, "vendor_dense_us": t_v * 1e6,
+                               "vendor_dense_over_bd": t_v / t_b}
+        extra["token_sweep_v3_kproj_bf16"] = sweep
+        log("sweep (BD / dense / vendor dense, us): " + ", ".join(
+            f"T={k[1:]} {v['bd_us']:.1f}/{v['dense_us']:.1f}/{v['vendor_dense_us']:.1f}" for k, v in sweep.items()))
+        del Cs_, Ws_
         # BD low-rank linear (config 5), fp16, timing-only weights
         T5, d_in, r5, d_out = 8192, 4096, 1024, 11008
         x5 = torch.randn((T5, d_in), device="cuda").to(torch.float16)
