@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the BD K/V up-projection hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--rotate R] [--no-graph] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--rotate R] [--no-graph] [--no-extras] [--no-sweep]
 
 A "step" is one bda_kv_project call over one batch of the DeepSeek-V2-Lite-shaped workload
 (T = 4096 tokens, d_c = 512, 16 K_nope + 16 V heads of 128, fp16): latent tile load, reduced-K MFMA
@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=16, help="distinct (c, out) buffer pairs")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="leave the token-count sweep out of the extras")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--prewarm-ms", type=float, default=200.0,
@@ -308,10 +309,11 @@ def main() -> int:
         # the throughput tables of Section "BDA Inference Efficiency"): BD projection, our dense
         # comparator, and the vendor GEMM (torch.matmul) doing the dense product
         Ns = 128 * 128
+        sweep_T = () if args.no_sweep else (1, 8, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192)
         Cs_ = dev(wl.to_storage(rng.standard_normal((K, Ns)) * 2.0, wl.BF16)[0], wl.BF16)
         Ws_ = dev(wl.to_storage(rng.standard_normal((d_c, Ns)) * 0.02, wl.BF16)[0], wl.BF16)
         sweep = {}
-        for Ts in (1, 8, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
+        for Ts in sweep_T:
             cs_ = dev(wl.to_storage(rng.standard_normal((Ts, d_c)), wl.BF16)[0], wl.BF16)
             os_ = torch.empty((Ts, Ns), dtype=torch.int16, device="cuda")
             n_s, n_w = (max(4, min(100, args.steps // 2)), 4) if Ts <= 2048 else (max(3, min(20, args.steps // 10)), 4)
@@ -325,9 +327,10 @@ def main() -> int:
             t_v = bench_small(lambda i, s: torch.matmul(cb_, Wb_, out=ob_), n_s, n_w)
             sweep[f"T{Ts}"] = {"bd_us": t_b * 1e6, "dense_us": t_d * 1e6, "vendor_dense_us": t_v * 1e6,
                                "vendor_dense_over_bd": t_v / t_b}
-        extra["token_sweep_v3_kproj_bf16"] = sweep
-        log("sweep (BD / dense / vendor dense, us): " + ", ".join(
-            f"T={k[1:]} {v['bd_us']:.1f}/{v['dense_us']:.1f}/{v['vendor_dense_us']:.1f}" for k, v in sweep.items()))
+        if sweep:
+            extra["token_sweep_v3_kproj_bf16"] = sweep
+            log("sweep (BD / dense / vendor dense, us): " + ", ".join(
+                f"T={k[1:]} {v['bd_us']:.1f}/{v['dense_us']:.1f}/{v['vendor_dense_us']:.1f}" for k, v in sweep.items()))
         del Cs_, Ws_
         # BD low-rank linear (config 5), fp16, timing-only weights
         T5, d_in, r5, d_out = 8192, 4096, 1024, 11008
