@@ -194,24 +194,41 @@ int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64
                             bda_dtype dtype, bda_dtype grad_dtype, void* stream);
 
 /*
- * Tuning / testing hook: which MFMA tile the fp16/bf16 kernels use.  0 = automatic (default: the
- * largest tile that still fills the chip), 1 = 128 x 128 tokens x columns, 2 = 256 x 256,
- * 3 = 256 x 256 with the general streaming kernel even where its lean variant would apply,
- * 4 = 128 x 256 with the lean streaming kernel where it applies (else as 2),
- * 5 = automatic, except that up to 128 tokens always take the wide-slice small-T kernel (128 columns per
- * workgroup up to 64 tokens, 64 columns above) wherever it applies (contraction d_c - d_h <= 384),
- * whatever the output width.
- * bda_kv_project_backward honours 1 (128 x 128 output tiles) and treats the rest as automatic.
- * Process-wide; returns the previous policy, or BDA_EINVAL.  Results do not depend on it beyond
- * float32 summation order inside a tile (none: the order over k is the same for every tile shape).
+ * The same three device calls with an explicit tile policy for this one call (tests, tuning and
+ * benchmarks of the individual kernels; the plain entry points are these with policy 0).  Nothing
+ * about the policy outlives the call and other threads' calls are unaffected.
+ *   0 = automatic (the largest tile that still fills the chip),
+ *   1 = 128 x 128 tokens x columns (register-staged MFMA kernel),
+ *   2 = 256 x 256 streaming tiles, lean variant where it applies,
+ *   3 = 256 x 256 with the general streaming kernel even where its lean variant would apply,
+ *   4 = 128 x 256 with the lean streaming kernel where it applies (else as 2),
+ *   5 = automatic, except that up to 128 tokens always take the wide-slice small-T kernel (128
+ *       columns per workgroup up to 64 tokens, 64 columns above) wherever it applies
+ *       (contraction d_c - d_h <= 384), whatever the output width.
+ * bda_kv_project_backward_ex honours 1 (128 x 128 output tiles) and treats the rest as automatic.
+ * Results do not depend on the policy beyond which kernel computes them (the order of the float32
+ * summation over k is the same for every tile shape).  Errors: as the plain call, plus BDA_EINVAL
+ * for a policy outside 0 .. 5.
  */
-int bda_set_tile_policy(int policy);
+int bda_kv_project_ex(const void* c, int64_t ldc, int64_t T, int d_c, int d_h,
+                      int G, const int* H, const int* basis_offset,
+                      const void* C, int64_t ldC, void* out, int64_t ld_out,
+                      bda_dtype dtype, bda_dtype out_dtype, void* stream, int tile_policy);
+int bda_dense_project_ex(const void* c, int64_t ldc, int64_t T, int d_c,
+                         const void* W, int64_t ldW, int64_t N,
+                         void* out, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
+                         void* stream, int tile_policy);
+int bda_kv_project_backward_ex(const void* c, int64_t ldc, const void* d_out, int64_t ld_dout,
+                               const void* C, int64_t ldC, int64_t T, int d_c, int d_h,
+                               int G, const int* H, const int* basis_offset,
+                               void* grad_c, int64_t ld_gc, void* grad_C, int64_t ld_gC,
+                               bda_dtype dtype, bda_dtype grad_dtype, void* stream, int tile_policy);
 
 /*
  * Launch description: which kernel, tile shape and schedule bda_kv_project / bda_dense_project
  * would use for a problem, from the same validation and tile choice as the real calls.  Runs on the
  * host only (no GPU needed, nothing is launched); pointers are assumed 16-byte aligned.  For
- * tests, tuning and documentation of the launch-shape rules; honours bda_set_tile_policy.
+ * tests, tuning and documentation of the launch-shape rules; `tile_policy` as in the *_ex calls.
  */
 typedef enum {
     BDA_KERNEL_NONE = 0,    /* nothing to launch (T = 0) */
@@ -239,10 +256,10 @@ typedef struct {
 
 int bda_kv_project_plan(int64_t T, int d_c, int d_h, int G, const int* H, const int* basis_offset,
                         int64_t ldc, int64_t ldC, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
-                        bda_launch_plan* plan);
+                        int tile_policy, bda_launch_plan* plan);
 
 int bda_dense_project_plan(int64_t T, int d_c, int64_t N, int64_t ldc, int64_t ldW, int64_t ld_out,
-                           bda_dtype dtype, bda_dtype out_dtype, bda_launch_plan* plan);
+                           bda_dtype dtype, bda_dtype out_dtype, int tile_policy, bda_launch_plan* plan);
 
 /* Message of the last failing call on this thread; never NULL ("" if none). */
 const char* bda_last_error(void);

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     bda_prepare, bda_prepare_lowrank, bda_prepare_device, bda_kv_project, bda_dense_project, bda_lowrank_linear,
     bda_kv_project_backward, bda_kv_project_plan, bda_dense_project_plan, LaunchPlan,
     KERNEL_NONE, KERNEL_GENERAL, KERNEL_MFMA, KERNEL_STREAM, KERNEL_LEAN, KERNEL_DECODE,
-    bda_set_tile_policy, bda_last_error, bda_version,
+    bda_kv_project_ex, bda_dense_project_ex, bda_kv_project_backward_ex, bda_last_error, bda_version,
 )

@@ -19,7 +19,8 @@ BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
 EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_kv_project", "bda_dense_project",
-           "bda_lowrank_linear", "bda_kv_project_backward", "bda_kv_project_plan", "bda_dense_project_plan", "bda_set_tile_policy", "bda_last_error", "bda_version")
+           "bda_lowrank_linear", "bda_kv_project_backward", "bda_kv_project_ex", "bda_dense_project_ex",
+           "bda_kv_project_backward_ex", "bda_kv_project_plan", "bda_dense_project_plan", "bda_last_error", "bda_version")
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _lib = None
@@ -81,12 +82,16 @@ def load():
     lib.bda_kv_project_backward.argtypes = [vp, i64, vp, i64, vp, i64, i64, c_int, c_int, c_int, ip, ip,
                                             vp, i64, vp, i64, c_int, c_int, vp]
     lib.bda_kv_project_plan.restype = c_int
-    lib.bda_kv_project_plan.argtypes = [i64, c_int, c_int, c_int, ip, ip, i64, i64, i64, c_int, c_int,
+    lib.bda_kv_project_plan.argtypes = [i64, c_int, c_int, c_int, ip, ip, i64, i64, i64, c_int, c_int, c_int,
                                         ctypes.POINTER(LaunchPlan)]
     lib.bda_dense_project_plan.restype = c_int
-    lib.bda_dense_project_plan.argtypes = [i64, c_int, i64, i64, i64, i64, c_int, c_int, ctypes.POINTER(LaunchPlan)]
-    lib.bda_set_tile_policy.restype = c_int
-    lib.bda_set_tile_policy.argtypes = [c_int]
+    lib.bda_dense_project_plan.argtypes = [i64, c_int, i64, i64, i64, i64, c_int, c_int, c_int, ctypes.POINTER(LaunchPlan)]
+    lib.bda_kv_project_ex.restype = c_int
+    lib.bda_kv_project_ex.argtypes = lib.bda_kv_project.argtypes + [c_int]
+    lib.bda_dense_project_ex.restype = c_int
+    lib.bda_dense_project_ex.argtypes = lib.bda_dense_project.argtypes + [c_int]
+    lib.bda_kv_project_backward_ex.restype = c_int
+    lib.bda_kv_project_backward_ex.argtypes = lib.bda_kv_project_backward.argtypes + [c_int]
     lib.bda_last_error.restype = ctypes.c_char_p
     lib.bda_last_error.argtypes = []
     lib.bda_version.restype = c_int
@@ -106,13 +111,6 @@ def bda_last_error() -> str:
 
 def bda_version() -> int:
     return int(load().bda_version())
-
-
-def bda_set_tile_policy(policy: int) -> int:
-    prev = int(load().bda_set_tile_policy(int(policy)))
-    if prev < 0:
-        raise BdaError(prev, bda_last_error())
-    return prev
 
 
 def _check(status: int) -> None:
@@ -194,6 +192,18 @@ def bda_kv_project(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],
                               dtype if out_dtype is None else out_dtype, stream or None))
 
 
+def bda_kv_project_ex(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],
+                      basis_offset: Sequence[int], C, ldC: int, out, ld_out: int, dtype: int,
+                      out_dtype: Optional[int] = None, stream: int = 0, tile_policy: int = 0) -> None:
+    lib = load()
+    G = len(H)
+    if len(basis_offset) != G:
+        raise ValueError("H and basis_offset must have one entry per group")
+    _check(lib.bda_kv_project_ex(_ptr(c), ldc, T, d_c, d_h, G, _int_array(H), _int_array(basis_offset),
+                                 _ptr(C), ldC, _ptr(out), ld_out, dtype,
+                                 dtype if out_dtype is None else out_dtype, stream or None, int(tile_policy)))
+
+
 def bda_prepare_device(W, ldw: int, w_dtype: int, d_c: int, H: int, d_h: int, basis_offset: int,
                        C, ldC: int, c_dtype: int, singular_head=None, stream: int = 0) -> None:
     lib = load()
@@ -206,6 +216,13 @@ def bda_dense_project(c, ldc: int, T: int, d_c: int, W, ldW: int, N: int, out, l
     lib = load()
     _check(lib.bda_dense_project(_ptr(c), ldc, T, d_c, _ptr(W), ldW, N, _ptr(out), ld_out, dtype,
                                  dtype if out_dtype is None else out_dtype, stream or None))
+
+
+def bda_dense_project_ex(c, ldc: int, T: int, d_c: int, W, ldW: int, N: int, out, ld_out: int,
+                         dtype: int, out_dtype: Optional[int] = None, stream: int = 0, tile_policy: int = 0) -> None:
+    lib = load()
+    _check(lib.bda_dense_project_ex(_ptr(c), ldc, T, d_c, _ptr(W), ldW, N, _ptr(out), ld_out, dtype,
+                                    dtype if out_dtype is None else out_dtype, stream or None, int(tile_policy)))
 
 
 def bda_lowrank_linear(x, ldx: int, T: int, d_in: int, r: int, d_out: int, basis_offset: int,
@@ -229,21 +246,38 @@ def bda_kv_project_backward(c, ldc: int, d_out, ld_dout: int, C, ldC: int, T: in
                                        dtype if grad_dtype is None else grad_dtype, stream or None))
 
 
+def bda_kv_project_backward_ex(c, ldc: int, d_out, ld_dout: int, C, ldC: int, T: int, d_c: int, d_h: int,
+                               H: Sequence[int], basis_offset: Sequence[int], grad_c, ld_gc: int,
+                               grad_C, ld_gC: int, dtype: int, grad_dtype: Optional[int] = None,
+                               stream: int = 0, tile_policy: int = 0) -> None:
+    lib = load()
+    G = len(H)
+    if len(basis_offset) != G:
+        raise ValueError("H and basis_offset must have one entry per group")
+    _check(lib.bda_kv_project_backward_ex(_ptr(c), ldc, _ptr(d_out), ld_dout, _ptr(C), ldC, T, d_c, d_h, G,
+                                          _int_array(H), _int_array(basis_offset), _ptr(grad_c), ld_gc,
+                                          _ptr(grad_C), ld_gC, dtype,
+                                          dtype if grad_dtype is None else grad_dtype, stream or None,
+                                          int(tile_policy)))
+
+
 def bda_kv_project_plan(T: int, d_c: int, d_h: int, H: Sequence[int], basis_offset: Sequence[int], dtype: int,
                         out_dtype: Optional[int] = None, ldc: Optional[int] = None, ldC: Optional[int] = None,
-                        ld_out: Optional[int] = None) -> dict:
+                        ld_out: Optional[int] = None, tile_policy: int = 0) -> dict:
     lib = load()
     N = int(sum(H)) * d_h
     plan = LaunchPlan()
     _check(lib.bda_kv_project_plan(T, d_c, d_h, len(H), _int_array(H), _int_array(basis_offset), ldc or d_c, ldC or N,
-                                   ld_out or N, dtype, dtype if out_dtype is None else out_dtype, ctypes.byref(plan)))
+                                   ld_out or N, dtype, dtype if out_dtype is None else out_dtype, int(tile_policy),
+                                   ctypes.byref(plan)))
     return plan.as_dict()
 
 
 def bda_dense_project_plan(T: int, d_c: int, N: int, dtype: int, out_dtype: Optional[int] = None,
-                           ldc: Optional[int] = None, ldW: Optional[int] = None, ld_out: Optional[int] = None) -> dict:
+                           ldc: Optional[int] = None, ldW: Optional[int] = None, ld_out: Optional[int] = None,
+                           tile_policy: int = 0) -> dict:
     lib = load()
     plan = LaunchPlan()
     _check(lib.bda_dense_project_plan(T, d_c, N, ldc or d_c, ldW or N, ld_out or N, dtype,
-                                      dtype if out_dtype is None else out_dtype, ctypes.byref(plan)))
+                                      dtype if out_dtype is None else out_dtype, int(tile_policy), ctypes.byref(plan)))
     return plan.as_dict()

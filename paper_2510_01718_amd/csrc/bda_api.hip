@@ -3,7 +3,6 @@
 
 #include <algorithm>
 #include <atomic>
-#include <mutex>
 
 #include "bda_gemm_kernels.hpp"
 #include "bda_decode.hpp"
@@ -14,7 +13,8 @@
 namespace bda {
 namespace {
 
-std::atomic<int> g_tile_policy{0};
+// Tile policy of the call in progress on this thread (0 = automatic; set by the *_ex entry points).
+thread_local int t_policy = 0;
 
 // Set by the *_plan entry points: the launchers then describe the launch instead of making it.
 thread_local bda_launch_plan* t_plan = nullptr;
@@ -27,20 +27,27 @@ bool plan_only(const GemmArgs& a, int kernel, int bt, int bn, int workgroups, in
     return true;
 }
 
+// Raises a kernel's dynamic LDS limit on the current device.  `state` remembers, per device, that
+// the attribute is set; a failed attempt is reported to its caller and tried again by the next call
+// (the attribute is idempotent, so two threads racing through here do no harm).
 template <typename K>
-int set_max_lds(K kernel, int bytes, std::once_flag& flag)
+int set_max_lds(K kernel, int bytes, LdsLimitState& state)
 {
-    hipError_t err = hipSuccess;
-    std::call_once(flag, [&] {
-        err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    });
-    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(err));
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return fail(BDA_EHIP, "hipGetDevice: %s", hipGetErrorString(err));
+    const bool tracked = dev >= 0 && dev < LdsLimitState::kMaxDevices;
+    if (tracked && state.done[dev].load(std::memory_order_acquire)) return BDA_OK;
+    err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err != hipSuccess) return fail(BDA_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(err));
+    if (tracked) state.done[dev].store(true, std::memory_order_release);
+    return BDA_OK;
 }
 
 template <typename X, typename OutT, int TT, int TN>
 int launch_mfma(GemmArgs& a, hipStream_t st)
 {
-    static std::once_flag once;
+    static LdsLimitState once;
     constexpr int lds = 2 * (64 * TT + 64 * TN) * kRowBytes;
     auto kern = gemm_mfma_kernel<X, OutT, TT, TN>;
     {
@@ -61,12 +68,12 @@ constexpr int kStreamSK = 64, kStreamNS = 2;
 template <typename X, typename OutT>
 int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
 {
-    static std::once_flag once, once_plain, once_half;
+    static LdsLimitState once, once_plain, once_half;
     constexpr int lds = kStreamNS * (256 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
     constexpr int lds_half = kStreamNS * (128 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
-    auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS, 0>;
-    auto kern_plain = gemm_plain_kernel<X, OutT, 0, 4>;
-    auto kern_half = gemm_plain_kernel<X, OutT, 0, 2>;
+    auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS>;
+    auto kern_plain = gemm_plain_kernel<X, OutT, 4>;
+    auto kern_half = gemm_plain_kernel<X, OutT, 2>;
     a.n_super_m = (a.m_tiles + a.sm - 1) / a.sm;
     a.n_super_n = (a.n_tiles + a.sn - 1) / a.sn;
     a.dh_magic = a.d_h > 0 ? (((uint64_t)1 << 40) + a.d_h - 1) / a.d_h : 0;
@@ -124,7 +131,7 @@ int decode_lds_bytes(int K)
 template <typename X, typename OutT, int NTB, bool TOK_LDS>
 int launch_decode_blocks(GemmArgs& a, hipStream_t st)
 {
-    static std::once_flag once;
+    static LdsLimitState once;
     auto kern = kv_decode_kernel<X, OutT, NTB, TOK_LDS>;
     const int lds = decode_lds_bytes<NTB, TOK_LDS>(a.K);
     const int per_xcd = (a.n_tiles + kNumXcd - 1) / kNumXcd;
@@ -138,7 +145,7 @@ int launch_decode_blocks(GemmArgs& a, hipStream_t st)
 template <typename X, typename OutT, int NTB, int CW>
 int launch_decode_wide_blocks(GemmArgs& a, hipStream_t st)
 {
-    static std::once_flag once;
+    static LdsLimitState once;
     auto kern = kv_decode_wide_kernel<X, OutT, NTB, CW>;
     constexpr int kspr = CW == 128 ? 1 : 2;                 // k-steps per request round
     const int nks = (a.K + 15) / 16;
@@ -243,7 +250,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     // blocks while every slice has a compute unit of its own (N = 4096: 5.8-7.3 against 10.6 with
     // 128-token tiles), then 64-column slices while those have (N = 12288 .. 16384: 8.4-9.4 against
     // 10.7-11.0), the tiles beyond (N = 24576: 11.3 against 15-16).
-    const int policy0 = g_tile_policy.load();
+    const int policy0 = t_policy;
     const bool small_policy = policy0 == 0 || policy0 == 5;
     int64_t n_slices128 = 0, n_slices64 = 0, n_slices32 = 0;
     for (int g = 0; g < G; ++g) {
@@ -340,17 +347,29 @@ int check_dtypes(const char* fn, int dtype, int out_dtype)
 
 }  // namespace
 
-int tile_policy() { return g_tile_policy.load(); }
+int tile_policy() { return t_policy; }
+
+PolicyScope::PolicyScope(int policy) : prev_(t_policy) { t_policy = policy; }
+PolicyScope::~PolicyScope() { t_policy = prev_; }
+
+int check_policy(const char* fn, int policy)
+{
+    return policy >= 0 && policy <= 5 ? BDA_OK : fail(BDA_EINVAL, "%s: tile_policy must be 0 .. 5 (got %d)", fn, policy);
+}
 
 }  // namespace bda
 
 using namespace bda;
 
-extern "C" int bda_set_tile_policy(int policy)
+extern "C" int bda_kv_project_ex(const void* c, int64_t ldc, int64_t T, int d_c, int d_h, int G,
+                                 const int* H, const int* basis_offset, const void* C, int64_t ldC,
+                                 void* out, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
+                                 void* stream, int tile_policy)
 {
     clear_error();
-    if (policy < 0 || policy > 5) return fail(BDA_EINVAL, "bda_set_tile_policy: policy must be 0 .. 5");
-    return g_tile_policy.exchange(policy);
+    if (int rc = check_policy("bda_kv_project_ex", tile_policy)) return rc;
+    PolicyScope scope(tile_policy);
+    return bda_kv_project(c, ldc, T, d_c, d_h, G, H, basis_offset, C, ldC, out, ld_out, dtype, out_dtype, stream);
 }
 
 extern "C" int bda_kv_project(const void* c, int64_t ldc, int64_t T, int d_c, int d_h, int G,
@@ -384,6 +403,16 @@ extern "C" int bda_kv_project(const void* c, int64_t ldc, int64_t T, int d_c, in
     a.M = T; a.K = K; a.d_h = d_h; a.a_skip = d_h; a.ident = 1;
     for (int g = 0; g < G; ++g) a.a_off[g] = basis_offset[g];
     return run_gemm(a, G, cols, dtype, out_dtype, (hipStream_t)stream);
+}
+
+extern "C" int bda_dense_project_ex(const void* c, int64_t ldc, int64_t T, int d_c, const void* W,
+                                    int64_t ldW, int64_t N, void* out, int64_t ld_out, bda_dtype dtype,
+                                    bda_dtype out_dtype, void* stream, int tile_policy)
+{
+    clear_error();
+    if (int rc = check_policy("bda_dense_project_ex", tile_policy)) return rc;
+    PolicyScope scope(tile_policy);
+    return bda_dense_project(c, ldc, T, d_c, W, ldW, N, out, ld_out, dtype, out_dtype, stream);
 }
 
 extern "C" int bda_dense_project(const void* c, int64_t ldc, int64_t T, int d_c, const void* W,
@@ -457,10 +486,12 @@ void* const kFakeD = (void*)((uintptr_t)3 << 40);
 
 extern "C" int bda_kv_project_plan(int64_t T, int d_c, int d_h, int G, const int* H, const int* basis_offset,
                                    int64_t ldc, int64_t ldC, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype,
-                                   bda_launch_plan* plan)
+                                   int tile_policy, bda_launch_plan* plan)
 {
     clear_error();
     if (!plan) return fail(BDA_EINVAL, "bda_kv_project_plan: NULL plan");
+    if (int rc = check_policy("bda_kv_project_plan", tile_policy)) return rc;
+    PolicyScope scope(tile_policy);
     *plan = bda_launch_plan{BDA_KERNEL_NONE, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     t_plan = plan;
     const int rc = bda_kv_project(kFakeA, ldc, T, d_c, d_h, G, H, basis_offset, kFakeB, ldC, kFakeD, ld_out, dtype, out_dtype, nullptr);
@@ -469,10 +500,12 @@ extern "C" int bda_kv_project_plan(int64_t T, int d_c, int d_h, int G, const int
 }
 
 extern "C" int bda_dense_project_plan(int64_t T, int d_c, int64_t N, int64_t ldc, int64_t ldW, int64_t ld_out,
-                                      bda_dtype dtype, bda_dtype out_dtype, bda_launch_plan* plan)
+                                      bda_dtype dtype, bda_dtype out_dtype, int tile_policy, bda_launch_plan* plan)
 {
     clear_error();
     if (!plan) return fail(BDA_EINVAL, "bda_dense_project_plan: NULL plan");
+    if (int rc = check_policy("bda_dense_project_plan", tile_policy)) return rc;
+    PolicyScope scope(tile_policy);
     *plan = bda_launch_plan{BDA_KERNEL_NONE, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     t_plan = plan;
     const int rc = bda_dense_project(kFakeA, ldc, T, d_c, kFakeB, ldW, N, kFakeD, ld_out, dtype, out_dtype, nullptr);

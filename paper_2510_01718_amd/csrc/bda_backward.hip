@@ -1,22 +1,25 @@
 // Device entry point for the gradients of the BD K/V projection: validation, tile grids, launches.
 #include <hip/hip_runtime.h>
 
-#include <mutex>
-
 #include "bda_bwd_kernels.hpp"
 #include "bda_internal.h"
 
 namespace bda {
 namespace {
 
+// (same contract as set_max_lds of the forward launchers: per device, retried after a failure)
 template <typename K>
-int allow_lds(K kernel, int bytes, std::once_flag& flag)
+int allow_lds(K kernel, int bytes, LdsLimitState& state)
 {
-    hipError_t err = hipSuccess;
-    std::call_once(flag, [&] {
-        err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    });
-    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(err));
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return fail(BDA_EHIP, "hipGetDevice: %s", hipGetErrorString(err));
+    const bool tracked = dev >= 0 && dev < LdsLimitState::kMaxDevices;
+    if (tracked && state.done[dev].load(std::memory_order_acquire)) return BDA_OK;
+    err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err != hipSuccess) return fail(BDA_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(err));
+    if (tracked) state.done[dev].store(true, std::memory_order_release);
+    return BDA_OK;
 }
 
 int launched()
@@ -28,7 +31,7 @@ int launched()
 template <typename X, typename OutT, int TT, int TN, bool WEIGHT>
 int launch_mfma(const BwdArgs& a, hipStream_t st)
 {
-    static std::once_flag once;
+    static LdsLimitState once;
     constexpr int lds = WEIGHT ? BwdWeightLds<TT, TN>::BYTES : BwdLds<TT, TN>::BYTES;
     const int total = a.m_tiles * a.n_tiles;
     const int grid = kNumXcd * ((total + kNumXcd - 1) / kNumXcd);
@@ -97,6 +100,19 @@ int launch_general(const BwdArgs& a, int dtype, int out_dtype, hipStream_t st)
 }  // namespace bda
 
 using namespace bda;
+
+extern "C" int bda_kv_project_backward_ex(const void* c, int64_t ldc, const void* d_out, int64_t ld_dout,
+                                          const void* C, int64_t ldC, int64_t T, int d_c, int d_h, int G,
+                                          const int* H, const int* basis_offset, void* grad_c, int64_t ld_gc,
+                                          void* grad_C, int64_t ld_gC, bda_dtype dtype, bda_dtype grad_dtype,
+                                          void* stream, int tile_policy)
+{
+    clear_error();
+    if (int rc = check_policy("bda_kv_project_backward_ex", tile_policy)) return rc;
+    PolicyScope scope(tile_policy);
+    return bda_kv_project_backward(c, ldc, d_out, ld_dout, C, ldC, T, d_c, d_h, G, H, basis_offset, grad_c, ld_gc,
+                                   grad_C, ld_gC, dtype, grad_dtype, stream);
+}
 
 extern "C" int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64_t ld_dout,
                                        const void* C, int64_t ldC, int64_t T, int d_c, int d_h, int G,

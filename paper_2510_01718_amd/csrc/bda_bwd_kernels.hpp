@@ -34,16 +34,6 @@
 
 namespace bda {
 
-// Working instrumentation (compiled only with -DBDA_BWD_TRACE): time stamps of workgroup 5.
-#ifdef BDA_BWD_TRACE
-__device__ unsigned long long bda_bwd_trace[8 * 1024];
-#define BWD_STAMP(tag) do { if (blockIdx.x == 5 && tr_n < 1020) { \
-    const unsigned long long tm_ = __builtin_readcyclecounter(); \
-    if (lane == 0) bda_bwd_trace[wave * 1024 + tr_n] = (tm_ << 8) | (tag); ++tr_n; } } while (0)
-#else
-#define BWD_STAMP(tag) do { } while (0)
-#endif
-
 struct BwdArgs {
     const void* c;    // T x d_c latent
     const void* g;    // T x N upstream gradient
@@ -546,13 +536,9 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
         return (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
     };
 
-    int tr_n = 0;
-    (void)tr_n;
     auto iteration = [&](auto set, auto stage, int it) {
         constexpr int S = decltype(set)::value, LS = decltype(stage)::value;
-        BWD_STAMP(1);
         load_chunk(set);
-        BWD_STAMP(2);
         if (2 * it + half < n_chunks) {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
@@ -569,14 +555,10 @@ __global__ __launch_bounds__(512) void bwd_weight_kernel(const BwdArgs p)
                     for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = X::mfma(fw[ni], ft[ti], acc[ni][ti]);
             }
         }
-        BWD_STAMP(3);
         store_chunk(std::integral_constant<int, (S + 1) % D>{}, std::integral_constant<int, 1 - LS>{});
-        BWD_STAMP(4);
         __syncthreads();
-        BWD_STAMP(5);
     };
 
-    BWD_STAMP(0);
     static_for<D>([&](auto r) { load_chunk(r); });
     store_chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     __syncthreads();

@@ -33,7 +33,7 @@ __device__ __forceinline__ void lds_dma_imm(u32x4 rsrc, uint32_t lds_base, uint3
         : "memory", "m0", "scc");
 }
 
-template <typename X, typename OutT, int DBG = 0, int TT_ = 4>
+template <typename X, typename OutT, int TT_ = 4>
 __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 {
     constexpr int SK = 64, WN = 4, NW = 8;
@@ -63,8 +63,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    int tr_n = 0;
-    (void)tr_n;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wt = wave / WN, wn = wave % WN;
     const int l31 = lane & 31, lhi = lane >> 5;
@@ -211,7 +209,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     };
     auto tok_load = [&](auto jc, const StreamTile& t, uint32_t lds_b, uint32_t soff, const uint32_t (&vt)[PIT]) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (j < PIT && !(DBG & 4)) lds_dma_imm<1024 * j>(t.rA, lds_b - tok_back, vt[j], soff);
+        if constexpr (j < PIT) lds_dma_imm<1024 * j>(t.rA, lds_b - tok_back, vt[j], soff);
     };
     // The four loads of a stage that go to the weight half of the slot: rows of the weight tile, or
     // (identity stage) the second 64 window columns of the token rows.  Uniform choice per stage.
@@ -233,7 +231,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     };
     auto wgt_load = [&](auto jc, const Second& z) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (!(DBG & 4)) lds_dma_imm<TOK_BYTES + 1024 * j>(z.r, j < PIT ? z.base : z.base_unused, z.v[j], z.so + (uint32_t)j * z.so_step);
+        lds_dma_imm<TOK_BYTES + 1024 * j>(z.r, j < PIT ? z.base : z.base_unused, z.v[j], z.so + (uint32_t)j * z.so_step);
     };
     auto produce_all = [&](const StreamTile& t, int k, uint32_t slot_b) {
         const uint32_t lds_b = slot_b + wave_lds;
@@ -252,14 +250,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     };
 
     // ---- consumer ---------------------------------------------------------------------------------
-    auto mm = [](u32x4 a, u32x4 b, f32x16 c) -> f32x16 {
-        if constexpr (DBG & 2) {
-            c[0] += __builtin_bit_cast(float, a[0] ^ b[0]);
-            return c;
-        } else {
-            return X::mfma(a, b, c);
-        }
-    };
+    auto mm = [](u32x4 a, u32x4 b, f32x16 c) -> f32x16 { return X::mfma(a, b, c); };
     f32x16 acc[TN][TT];
     const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -337,7 +328,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         const int jc = cur.j_lo + (kc - nk) * (2 * SK) + half_cur * SK;
         u32x4 idf[2];
         if constexpr (!REG) make_idf(idf);
-        BDA_STAMP(1);
         // The two waves of a SIMD run the same code and the older one wins every arbitration, so it
         // runs ahead to the barrier and leaves the other to work through the stage alone.  Alternating
         // the priority by half stages keeps them side by side (measured: 4-8 % faster).
@@ -365,11 +355,8 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         uint32_t vt[PIT];
         tok_voffs(pt, pk, vt);
         const Second z = second_set(pt, pk, lds_b, ts, vt);
-        BDA_STAMP(2);
         if (FIRST && relaxed) wait_vmcnt<STORES>(); else wait_vmcnt<0>();
-        BDA_STAMP(3);
         __syncthreads();
-        BDA_STAMP(4);
         if (wt == 0) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
         if constexpr (REG && TT == 4) {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
@@ -392,7 +379,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt);
             tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt);
         }
-        BDA_STAMP(5);
         // first fragments of the next stage, out of the other slot
         if (next_regular) read_w(0, fw0);
         read_t(0, ft0, off_next);
@@ -424,25 +410,17 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         slot_b = (uint32_t)STAGE_BYTES - slot_b;
     };
 
-    BDA_STAMP(0);
     StreamTile cur = setup();
-    BDA_STAMP(10);
     // prologue: the first two stages of the first tile; every wave's first stage is queued before
     // anybody's second
     produce_all(cur, 0, 0u);
-    BDA_STAMP(11);
     __builtin_amdgcn_s_barrier();
-    BDA_STAMP(12);
     produce_all(cur, 1, (uint32_t)STAGE_BYTES);
     clear_acc();
-    BDA_STAMP(13);
     wait_vmcnt<PIT + PIW>();
-    BDA_STAMP(14);
     __syncthreads();
-    BDA_STAMP(15);
     read_w(0, fw0);
     read_t(0, ft0);
-    BDA_STAMP(16);
 
     const std::true_type REGULAR{};
     const std::false_type IDENTITY{};
@@ -452,7 +430,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll 1
     for (int round = 0; round < n_rounds; ++round) {
         const StreamTile nxt = setup();
-        BDA_STAMP(17);
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {      // d_h >= 64 is a multiple of 64 and rel_blk0 < d_h
             rel_blk[ni] = cur.rel_blk0 + 32 * ni;
@@ -471,23 +448,13 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll 1
         for (; kc < S; ++kc) stage(IDENTITY, std::false_type{}, cur, kc, nxt, kc - split, false);
 
-        BDA_STAMP(6);
         // ---- epilogue ---------------------------------------------------------------------------
         // rows past the end of the tensor and tiles outside the grid fall outside rD's range
         const __amdgpu_buffer_rsrc_t rD = make_rsrc(
             (char*)q.D + cur.d_off * (int64_t)sizeof(OutT),
             cur.cols_left > 0 ? ((cur.rows_left - 1) * q.ldd + cur.cols_left) * (int64_t)sizeof(OutT) : 0);
         const uint32_t ep_row_step = 32u * (uint32_t)(q.ldd * sizeof(OutT));
-        if constexpr (DBG & 1) {
-            float sum = 0.f;
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sum += acc[ni][ti][r];
-            if (sum == 12345.678f) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, sum), rD, 0, 0, 0);
-        } else if constexpr (sizeof(OutT) == 4) {
+        if constexpr (sizeof(OutT) == 4) {
             int eln = lane;
             asm volatile("" : "+v"(eln));
             uint32_t ep_row = (uint32_t)(wt * (32 * TT) + (eln & 31)) * (uint32_t)(q.ldd * 4) + (uint32_t)(wn * (32 * TN) + (eln >> 5) * 4) * 4u;
@@ -557,12 +524,10 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
                 }
             }
         }
-        BDA_STAMP(7);
         clear_acc();
         cur = nxt;
     }
     wait_vmcnt<0>();
-    BDA_STAMP(8);
 }
 
 }  // namespace bda

@@ -32,8 +32,6 @@
 // about, and it would wait for it - and with it for every DMA load - inside the k loop.  Values
 // needed only in one phase (identity fragments, store addresses) are therefore rebuilt there from
 // a copy of the lane id that the optimiser cannot see through.
-//
-// Defining BDA_TRACE adds per-wave time stamps (s_memtime) for profiling experiments.
 #pragma once
 #include <type_traits>
 
@@ -129,15 +127,6 @@ __device__ __forceinline__ int tok_swz(int r)
 // different banks.
 __device__ __forceinline__ int wgt_swz(int k) { return (k & 3) * 5; }
 
-#ifdef BDA_TRACE
-__device__ unsigned long long bda_trace[8 * 1024];
-#define BDA_STAMP(tag) do { if constexpr (DBG & 16) { if (blockIdx.x == 9 && tr_n < 1020) { \
-    const unsigned long long tm_ = __builtin_readcyclecounter(); \
-    if (lane == 0) bda_trace[wave * 1024 + tr_n] = (tm_ << 8) | (tag); ++tr_n; } } } while (0)
-#else
-#define BDA_STAMP(tag) do { } while (0)
-#endif
-
 struct StreamTile {
     u32x4 rA, rB;              // producer descriptors (range 0 for a tile outside the grid)
     int64_t d_off;             // element offset of the tile's first output
@@ -148,9 +137,6 @@ struct StreamTile {
     int rel_blk0;              // slice column of the first 32-column block of the calling wave's part
 };
 
-// DBG is for timing experiments only (0 in the library): bit 0 drops the result stores, bit 1 the
-// MFMAs, bit 2 the global loads, bit 4 records time stamps (with BDA_TRACE).
-//
 // WT x WN waves share the 256 x 256 tile: 2 x 2 waves of 128 x 128 (one wave per SIMD) or 2 x 4 waves
 // of 128 tokens x 64 columns (two waves per SIMD, so that one wave's LDS reads, barrier wait and
 // address arithmetic overlap the other's MFMAs).
@@ -161,7 +147,7 @@ struct StreamTile {
 // Host contract: p.n_stage_id = identity stages per tile (the same for every tile of a launch),
 // stages per tile S = ceil(K / SK) + n_stage_id >= NS; grid = 8 * sm * sn workgroups;
 // dynamic LDS = NS * (256 * 2 SK + SK * 512) + 4096 * waves.
-template <typename X, typename OutT, int WT, int WN, int SK, int NS, int DBG = 0>
+template <typename X, typename OutT, int WT, int WN, int SK, int NS>
 __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArgs p)
 {
     constexpr int kStageK = SK, kStages = NS, kAhead = NS - 1;
@@ -201,8 +187,6 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    int tr_n = 0;
-    (void)tr_n;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wt = wave / WN, wn = wave % WN;
     const int l31 = lane & 31, lhi = lane >> 5;
@@ -393,15 +377,13 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     };
     // load j (0 .. LOADS-1) of the stage whose vector offsets prepare_offsets has set
     auto issue_load = [&](const StreamTile& t, const StageOff& o, int g, int j) {
-        if constexpr (!(DBG & 4)) {
-            const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
-            if (j < PIT) {
-                lds_dma1s(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, vo_tok[j < PIT ? j : 0], o.tok_soff);
-            } else {
-                const int jj = j >= PIT ? j - PIT : 0;
-                lds_dma1s(o.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * jj, vo_wgt[jj],
-                          o.plain ? o.wgt_soff + (uint32_t)(2 * jj) * wgt_row_bytes : 0u);
-            }
+        const uint32_t lds_slot = (uint32_t)((g & (kStages - 1)) * STAGE_BYTES);
+        if (j < PIT) {
+            lds_dma1s(t.rA, lds_slot + (uint32_t)wave * (1024u * PIT) + 1024u * j, vo_tok[j < PIT ? j : 0], o.tok_soff);
+        } else {
+            const int jj = j >= PIT ? j - PIT : 0;
+            lds_dma1s(o.rB, lds_slot + (uint32_t)TOK_BYTES + (uint32_t)wave * (1024u * PIW) + 1024u * jj, vo_wgt[jj],
+                      o.plain ? o.wgt_soff + (uint32_t)(2 * jj) * wgt_row_bytes : 0u);
         }
     };
     auto produce = [&](const StreamTile& t, int k, int g) {
@@ -417,14 +399,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     // barrier, the producer's address arithmetic and the DMA issue sit behind queued MFMAs:
     //     read(stage i, k-step 1) | MFMA(stage i, k-step 0) | wait + barrier + produce(stage i + 4)
     //     | read(stage i + 1, k-step 0) | MFMA(stage i, k-step 1) | ...
-    auto mm = [](u32x4 a, u32x4 b, f32x16 c) -> f32x16 {
-        if constexpr (DBG & 2) {
-            c[0] += __builtin_bit_cast(float, a[0] ^ b[0]);     // keeps the operands alive
-            return c;
-        } else {
-            return X::mfma(a, b, c);
-        }
-    };
+    auto mm = [](u32x4 a, u32x4 b, f32x16 c) -> f32x16 { return X::mfma(a, b, c); };
     f32x16 acc[TN][TT];
     const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -500,7 +475,6 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         u32x4 idf[2];
         if constexpr (!REG) make_idf(idf);
         static_assert(KS % 2 == 0, "fragment sets alternate");
-        BDA_STAMP(1);
         // addresses of the stage requested after this stage's barrier: worked out here, behind the
         // MFMAs of the first k-steps, so that nothing but the loads themselves follows the barrier
         const StageOff so = stage_offsets(pt, pk);
@@ -518,18 +492,14 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         // last read of this stage's slot, then the slot is free once every wave is here
         if constexpr (REG) read_w(sb, KS - 1, fw1);
         read_t(sb, KS - 1, ft1);
-        BDA_STAMP(2);
         if (relaxed) wait_vmcnt<WAIT_AFTER_STORES>(); else wait_vmcnt<WAIT_STEADY>();
-        BDA_STAMP(3);
         __syncthreads();
-        BDA_STAMP(4);
         if constexpr (REG) mma_regular_loads(fw0, ft0, pt, so, g, 0);
         else {
             mma_identity(idf, jc + 16 * (KS - 2), ft0);
 #pragma unroll
             for (int j = 0; j < LOADS / 2; ++j) issue_load(pt, so, g, j);
         }
-        BDA_STAMP(5);
         if (next_regular) read_w(nb, 0, fw0);
         read_t(nb, 0, ft0);
         if constexpr (REG) mma_regular_loads(fw1, ft1, pt, so, g, LOADS / 2);
@@ -540,25 +510,19 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         }
     };
 
-    BDA_STAMP(0);
     StreamTile cur = setup();
     int g = 0;
     // prologue: the first kStages stages of the first tile
 #pragma unroll 1
-    BDA_STAMP(9);
     for (int k = 0; k < kStages; ++k) {
         produce(cur, k, k);
         if (k == 0) __builtin_amdgcn_s_barrier();   // the first stage of all waves goes ahead of everything else
     }
-    BDA_STAMP(10);
     clear_acc();
     wait_vmcnt<(kStages - 1) * LOADS>();
-    BDA_STAMP(11);
     __syncthreads();
-    BDA_STAMP(12);
     read_w(slot_base(0), 0, fw0);
     read_t(slot_base(0), 0, ft0);
-    BDA_STAMP(13);
 
     const std::true_type REGULAR{};
     const std::false_type IDENTITY{};
@@ -568,7 +532,6 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
 #pragma unroll 1
     for (int round = 0; round < n_rounds; ++round) {
         const StreamTile nxt = setup();
-        BDA_STAMP(14);
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) {      // d_h >= 32 is a multiple of 32 and rel_blk0 < d_h
             rel_blk[ni] = cur.rel_blk0 + 32 * ni;
@@ -586,7 +549,6 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
 #pragma unroll 1
         for (; kc < S; ++kc, ++g) stage(IDENTITY, cur, kc, g, nxt, kc - split, after_tile && kc < (kAhead > 1 ? kAhead : 1));
 
-        BDA_STAMP(6);
         // ---- epilogue ---------------------------------------------------------------------------
         // rows past the end of the tensor and tiles outside the grid fall outside rD's range
         const __amdgpu_buffer_rsrc_t rD = make_rsrc(
@@ -594,16 +556,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
             cur.cols_left > 0 ? ((cur.rows_left - 1) * q.ldd + cur.cols_left) * (int64_t)sizeof(OutT) : 0);
         const uint32_t ep_row_step = 32u * (uint32_t)(q.ldd * sizeof(OutT));
         const bool full = cur.cols_left == BN;      // uniform; a group may end inside its last tile
-        if constexpr (DBG & 1) {
-            float sum = 0.f;
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sum += acc[ni][ti][r];
-            if (sum == 12345.678f) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, sum), rD, 0, 0, 0);
-        } else if constexpr (sizeof(OutT) == 4) {
+        if constexpr (sizeof(OutT) == 4) {
             int eln = lane;
             asm volatile("" : "+v"(eln));
             uint32_t ep_row = (uint32_t)(wt * (32 * TT) + (eln & 31)) * (uint32_t)(q.ldd * 4) + (uint32_t)(wn * (32 * TN) + (eln >> 5) * 4) * 4u;
@@ -675,12 +628,10 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
                 }
             }
         }
-        BDA_STAMP(7);
         clear_acc();
         cur = nxt;
     }
     wait_vmcnt<0>();
-    BDA_STAMP(8);
 }
 
 }  // namespace bda

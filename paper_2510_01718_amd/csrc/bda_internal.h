@@ -1,5 +1,6 @@
 // Internal helpers shared by the translation units of libbda (not part of the public ABI).
 #pragma once
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -28,8 +29,25 @@ inline size_t dtype_size(int dt)
     }
 }
 
-// The process-wide tile policy set by bda_set_tile_policy (0 = automatic).
+// Tile policy of the call in progress on this thread (0 = automatic).  The *_ex entry points set it
+// for the duration of their call through a PolicyScope; nothing outlives the call.
 int tile_policy();
+int check_policy(const char* fn, int policy);
+class PolicyScope {
+public:
+    explicit PolicyScope(int policy);
+    ~PolicyScope();
+    PolicyScope(const PolicyScope&) = delete;
+    PolicyScope& operator=(const PolicyScope&) = delete;
+private:
+    int prev_;
+};
+
+// Per-device "the dynamic LDS limit of this kernel has been raised" flags (see set_max_lds).
+struct LdsLimitState {
+    static constexpr int kMaxDevices = 64;
+    std::atomic<bool> done[kMaxDevices] = {};
+};
 
 // Byte range [lo, hi) of a rows x cols matrix with leading dimension ld (elements of esz bytes).
 struct Span {

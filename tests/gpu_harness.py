@@ -42,8 +42,10 @@ def stream() -> int:
 
 
 def kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, out_dtype=None, ldc=None, ldC=None,
-               ld_out=None, fill=None):
-    """Runs bda_kv_project on stored inputs and returns (float64 output, raw device tensor)."""
+               ld_out=None, fill=None, policy=0, extra_rows=0):
+    """Runs bda_kv_project (bda_kv_project_ex for a tile policy other than 0) on stored inputs and
+    returns (float64 output, raw device tensor).  `extra_rows` rows are allocated past the T the call
+    is given (with `fill`, a guard against writes past the last token)."""
     out_dtype = dtype if out_dtype is None else out_dtype
     T = c_stored.shape[0]
     N = int(sum(H)) * d_h
@@ -52,7 +54,10 @@ def kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, out_dtype=None, ldc
     ld_out = ld_out or N
     c_d = to_device(c_stored, dtype, ldc)
     C_d = to_device(C_stored, dtype, ldC)
-    out_d = new_out(max(T, 1), ld_out, out_dtype, fill)
-    bda.bda_kv_project(c_d, ldc, T, d_c, d_h, H, offs, C_d, ldC, out_d, ld_out, dtype, out_dtype, stream())
+    out_d = new_out(max(T, 1) + extra_rows, ld_out, out_dtype, fill)
+    if policy:
+        bda.bda_kv_project_ex(c_d, ldc, T, d_c, d_h, H, offs, C_d, ldC, out_d, ld_out, dtype, out_dtype, stream(), policy)
+    else:
+        bda.bda_kv_project(c_d, ldc, T, d_c, d_h, H, offs, C_d, ldC, out_d, ld_out, dtype, out_dtype, stream())
     torch.cuda.synchronize()
     return to_host64(out_d[:T], out_dtype, N), out_d

@@ -33,7 +33,7 @@ def _inputs(seed, T, d_c, d_h, H, dtype, c_scale=1.0, C_scale=0.25):
     return (c_s, c64), (g_s, g64), (C_s, C64)
 
 
-def _backward(c_s, g_s, C_s, T, d_c, d_h, H, offs, dtype, grad_dtype=None, pad=0, want=(True, True), fill=None):
+def _backward(c_s, g_s, C_s, T, d_c, d_h, H, offs, dtype, grad_dtype=None, pad=0, want=(True, True), fill=None, policy=0):
     grad_dtype = dtype if grad_dtype is None else grad_dtype
     N = sum(H) * d_h
     K = d_c - d_h
@@ -43,8 +43,12 @@ def _backward(c_s, g_s, C_s, T, d_c, d_h, H, offs, dtype, grad_dtype=None, pad=0
     C_d = gh.to_device(C_s, dtype, ldC)
     gc_d = gh.new_out(max(T, 1), ld_gc, grad_dtype, fill) if want[0] else None
     gC_d = gh.new_out(K, ld_gC, grad_dtype, fill) if want[1] else None
-    bda.bda_kv_project_backward(c_d if want[1] else None, ldc, g_d, ldg, C_d if want[0] else None, ldC,
-                                T, d_c, d_h, H, offs, gc_d, ld_gc, gC_d, ld_gC, dtype, grad_dtype, gh.stream())
+    if policy:
+        bda.bda_kv_project_backward_ex(c_d if want[1] else None, ldc, g_d, ldg, C_d if want[0] else None, ldC,
+                                       T, d_c, d_h, H, offs, gc_d, ld_gc, gC_d, ld_gC, dtype, grad_dtype, gh.stream(), policy)
+    else:
+        bda.bda_kv_project_backward(c_d if want[1] else None, ldc, g_d, ldg, C_d if want[0] else None, ldC,
+                                    T, d_c, d_h, H, offs, gc_d, ld_gc, gC_d, ld_gC, dtype, grad_dtype, gh.stream())
     torch.cuda.synchronize()
     gc = gh.to_host64(gc_d[:T], grad_dtype, d_c) if want[0] else None
     gC = gh.to_host64(gC_d, grad_dtype, N) if want[1] else None
@@ -54,11 +58,7 @@ def _backward(c_s, g_s, C_s, T, d_c, d_h, H, offs, dtype, grad_dtype=None, pad=0
 def _check(T, d_c, d_h, H, offs, dtype, grad_dtype=None, pad=0, policy=0, seed=5, what=""):
     (c_s, c64), (g_s, g64), (C_s, C64) = _inputs(seed, T, d_c, d_h, H, dtype)
     ref_c, ref_C = oracle.kv_project_backward(c64, g64, C64, d_h, H, offs)
-    bda.bda_set_tile_policy(policy)
-    try:
-        gc, gC, _, _ = _backward(c_s, g_s, C_s, T, d_c, d_h, H, offs, dtype, grad_dtype, pad)
-    finally:
-        bda.bda_set_tile_policy(0)
+    gc, gC, _, _ = _backward(c_s, g_s, C_s, T, d_c, d_h, H, offs, dtype, grad_dtype, pad, policy=policy)
     gd = dtype if grad_dtype is None else grad_dtype
     tag = f"{what} T={T} d_c={d_c} d_h={d_h} H={H} offs={offs} dtype={dtype}/{gd} policy={policy}"
     if T:

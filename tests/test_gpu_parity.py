@@ -33,11 +33,7 @@ def _prepare_stored(W, d_c, H, d_h, offs, dtype):
 def _run_kv_case(w, offs, out_dtype=None, policy=0, **ld):
     C_stored, C64 = _prepare_stored(w.W, w.d_c, w.H, w.d_h, offs, w.dtype)
     ref = oracle.kv_project(w.c, C64, w.d_h, w.H, offs)
-    bda.bda_set_tile_policy(policy)
-    try:
-        got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, out_dtype, **ld)
-    finally:
-        bda.bda_set_tile_policy(0)
+    got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, out_dtype, policy=policy, **ld)
     od = w.dtype if out_dtype is None else out_dtype
     return assert_parity(got, ref, w.d_h, w.dtype, od, f"{w.name} offs={offs} policy={policy}")
 
@@ -122,11 +118,8 @@ def test_small_T_kernels_random_shapes(seed):
         ref = oracle.kv_project(c64, C64, d_h, H, offs)
         for policy in (0, 5):
             what = f"seed {seed} case {case} policy {policy}: T={T} d_c={d_c} d_h={d_h} H={H} offs={offs} ld=({ldc},{ldC},{ld_out})"
-            bda.bda_set_tile_policy(policy)
-            try:
-                got, raw = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0)
-            finally:
-                bda.bda_set_tile_policy(0)
+            got, raw = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0,
+                                     policy=policy)
             assert_parity(got, ref, d_h, dtype, dtype, what)
             if ld_out > N:
                 pad = raw[:, N:].cpu().numpy()
@@ -156,11 +149,8 @@ def test_tile_kernels_random_shapes(seed):
         ref = oracle.kv_project(c64, C64, d_h, H, offs)
         for policy in (0, 1, 2, 3, 4, 5):
             what = f"seed {seed} case {case} policy {policy}: T={T} d_c={d_c} d_h={d_h} H={H} offs={offs} ld=({ldc},{ldC},{ld_out})"
-            bda.bda_set_tile_policy(policy)
-            try:
-                got, _ = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0)
-            finally:
-                bda.bda_set_tile_policy(0)
+            got, _ = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0,
+                                   policy=policy)
             assert_parity(got, ref, d_h, dtype, dtype, what)
 
 
@@ -273,11 +263,7 @@ def test_dense_many_stages_streaming(policy):
     Ws, W64 = wl.to_storage(W, wl.F16)
     x_d, W_d = gh.to_device(xs, wl.F16), gh.to_device(Ws, wl.F16)
     out_d = gh.new_out(T, N, wl.F16)
-    bda.bda_set_tile_policy(policy)
-    try:
-        bda.bda_dense_project(x_d, K, T, K, W_d, N, N, out_d, N, wl.F16, stream=gh.stream())
-    finally:
-        bda.bda_set_tile_policy(0)
+    bda.bda_dense_project_ex(x_d, K, T, K, W_d, N, N, out_d, N, wl.F16, stream=gh.stream(), tile_policy=policy)
     torch.cuda.synchronize()
     assert_parity(gh.to_host64(out_d, wl.F16), oracle.dense_project(x64, W64), N, wl.F16, wl.F16, "dense K=1024")
 
@@ -308,10 +294,8 @@ def test_kv_strided_buffers_and_untouched_padding():
     ref = oracle.kv_project(w.c, C64, w.d_h, w.H, offs)
     N = w.N
     for policy in (1, 2):
-        bda.bda_set_tile_policy(policy)
         got, raw = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype,
-                                 ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24, fill=-7.0)
-        bda.bda_set_tile_policy(0)
+                                 ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24, fill=-7.0, policy=policy)
         assert_parity(got, ref, w.d_h, w.dtype, w.dtype, "strided")
         pad = raw[:, N:].cpu().numpy()
         assert np.all(pad == np.float16(-7.0)), "columns beyond N were written"
@@ -329,15 +313,12 @@ def test_small_T_kernels_strided_buffers_and_exact_copy(T, policy):
     C_stored, C64 = _prepare_stored(w.W, w.d_c, w.H, w.d_h, offs, w.dtype)
     ref = oracle.kv_project(w.c, C64, w.d_h, w.H, offs)
     N = w.N
-    bda.bda_set_tile_policy(policy)
-    try:
-        assert bda.bda_kv_project_plan(T, 512, 128, w.H, offs, w.dtype, ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24)["kernel"] == bda.KERNEL_DECODE
-        got, raw = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype,
-                                 ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24, fill=-7.0)
-        zero_C, _ = wl.to_storage(np.zeros((384, N)), w.dtype)
-        copy, _ = gh.kv_project(w.c_stored, zero_C, w.d_c, w.d_h, w.H, offs, w.dtype)
-    finally:
-        bda.bda_set_tile_policy(0)
+    assert bda.bda_kv_project_plan(T, 512, 128, w.H, offs, w.dtype, ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24,
+                                   tile_policy=policy)["kernel"] == bda.KERNEL_DECODE
+    got, raw = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype,
+                             ldc=w.d_c + 64, ldC=N + 8, ld_out=N + 24, fill=-7.0, policy=policy)
+    zero_C, _ = wl.to_storage(np.zeros((384, N)), w.dtype)
+    copy, _ = gh.kv_project(w.c_stored, zero_C, w.d_c, w.d_h, w.H, offs, w.dtype, policy=policy)
     assert_parity(got, ref, w.d_h, w.dtype, w.dtype, "strided small T")
     pad = raw[:, N:].cpu().numpy()
     assert np.all(pad == np.float16(-7.0)), "columns beyond N were written"
@@ -366,9 +347,7 @@ def test_zero_C_copies_basis_slice_bit_exactly(dtype):
                               dtype=dtype, seed=17)
     C_stored, _ = wl.to_storage(np.zeros((384, w.N)), dtype)
     for policy, offs in ((1, [64, 384]), (2, [64, 384]), (4, [64, 384]), (2, [40, 376]), (4, [8, 200])):
-        bda.bda_set_tile_policy(policy)
-        got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, dtype)
-        bda.bda_set_tile_policy(0)
+        got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, dtype, policy=policy)
         for h in range(4):
             off = offs[0] if h < 2 else offs[1]
             assert np.array_equal(got[:, h * 128:(h + 1) * 128], w.c[:, off:off + 128]), (dtype, h, policy)
@@ -421,9 +400,7 @@ def test_dense_project(dtype, policy):
     ref = oracle.dense_project(w.c, W64)
     c_d, W_d = gh.to_device(w.c_stored, dtype), gh.to_device(W_stored, dtype)
     out_d = gh.new_out(w.T, w.N, dtype)
-    bda.bda_set_tile_policy(policy)
-    bda.bda_dense_project(c_d, 512, w.T, 512, W_d, w.N, w.N, out_d, w.N, dtype, stream=gh.stream())
-    bda.bda_set_tile_policy(0)
+    bda.bda_dense_project_ex(c_d, 512, w.T, 512, W_d, w.N, w.N, out_d, w.N, dtype, stream=gh.stream(), tile_policy=policy)
     torch.cuda.synchronize()
     assert_parity(gh.to_host64(out_d, dtype), ref, 128, dtype, dtype, "dense")
 
@@ -441,13 +418,9 @@ def test_dense_project_few_tokens(T, policy):
     out_d = gh.new_out(w.T, w.N, dtype)
     p = bda.bda_dense_project_plan(T, 320, w.N, dtype)
     assert p["kernel"] == bda.KERNEL_DECODE
-    bda.bda_set_tile_policy(policy)
-    try:
-        if policy == 5 and T <= 64:
-            assert bda.bda_dense_project_plan(T, 320, w.N, dtype)["tile_columns"] == 128
-        bda.bda_dense_project(c_d, 320, w.T, 320, W_d, w.N, w.N, out_d, w.N, dtype, stream=gh.stream())
-    finally:
-        bda.bda_set_tile_policy(0)
+    if policy == 5 and T <= 64:
+        assert bda.bda_dense_project_plan(T, 320, w.N, dtype, tile_policy=policy)["tile_columns"] == 128
+    bda.bda_dense_project_ex(c_d, 320, w.T, 320, W_d, w.N, w.N, out_d, w.N, dtype, stream=gh.stream(), tile_policy=policy)
     torch.cuda.synchronize()
     assert_parity(gh.to_host64(out_d, dtype), ref, 64, dtype, dtype, "dense few tokens")
 
