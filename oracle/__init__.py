@@ -5,10 +5,12 @@ Nothing in the product may import this package: only `tests/`, `__graft_entry__.
 
 Two layers, both float64:
 
-* The paper's algorithms written out literally with numpy (`bd_decompose_row`, `bd_reconstruct_row`,
-  `bd_decompose_col`, `attention_prepare_qk`, `attention_prepare_vo`): Algorithms "BD Decomposition
-  (Row)", "BD Reconstruction (Row)", "BD Attention Preparation (QK)" and Appendix "BD for VO in MHA".
-  They work on the d x d product matrices, so they are for small and medium sizes.
+* Basis Decomposition on explicit matrices with numpy (`bd_window`: one candidate window, solve
+  plus residual; `bd_assemble`: the matrix a BD pair stands for; `bd_decompose`: the best of the
+  candidate windows; `attention_prepare_qk`, `attention_prepare_vo`: one window for all heads by
+  the mean residual), covering Eq. bd_identity, Algorithms "BD Decomposition (Row)", "BD
+  Reconstruction (Row)", "BD Attention Preparation (QK)" and Appendix "BD for VO in MHA".  They
+  work on the d x d product matrices, so they are for small and medium sizes.
 * The per-head closed form the product path is specified by (`prepare`, `prepare_lowrank`):
   C_h = W_h[Bbar,:] W_h[B,:]^{-1}, which follows from the column-first BD of W_q^h (W_k^h)^T
   (Eq. qk_bd_single) and the row-first BD of W_v^h W_o^h (Appendix "BD for VO in MHA"), and the
@@ -101,111 +103,118 @@ def round_store(x: np.ndarray, dtype: int) -> np.ndarray:
         _, e = np.frexp(x)
         s = np.maximum(e - 8, -133)
         y = np.ldexp(np.rint(np.ldexp(x, -s)), s)
+        y = np.where(np.abs(y) >= 2.0 ** 128, np.copysign(np.inf, x), y)   # past the largest finite value: +-inf, as IEEE rounding overflows
         return np.where(np.isfinite(x), y, x)
     raise ValueError("dtype")
 
 
 # ------------------------------------------------------------------------------------------------
-# the paper's algorithms, literally
+# Basis Decomposition of a matrix for one candidate window, and the choice among candidates
 # ------------------------------------------------------------------------------------------------
-def _solve_right(Bm: np.ndarray, R: np.ndarray) -> np.ndarray:
+# Eq. bd_identity has four forms (row/column basis, first/last); all are "a contiguous window of r
+# rows (columns) is the basis B, every other row (column) is a combination C of it".  One routine
+# handles a window at any start; first-r is start 0, last-r is start m - r.  Algorithms "BD
+# Decomposition (Row)" / "BD Reconstruction (Row)" and their column twins are this routine looped
+# over the two (or more) candidate windows with the smallest Frobenius residual kept.
+ROWS, COLS = 0, 1
+
+
+def _combine(Bm: np.ndarray, R: np.ndarray) -> np.ndarray:
     """C with C @ Bm = R, Bm of full row rank (r x n, n >= r): least squares on the transposed
     system; exact when R lies in the row space of Bm, which BD guarantees."""
     sol, *_ = np.linalg.lstsq(Bm.T, R.T, rcond=None)
     return sol.T
 
 
-def bd_reconstruct_row(tag: int, Bm: np.ndarray, C: np.ndarray) -> np.ndarray:
-    """Algorithm "BD Reconstruction (Row)": W <- [B; C B] (FIRST) or [C B; B] (LAST)."""
-    if tag == FIRST:
-        return np.vstack([Bm, C @ Bm])
-    return np.vstack([C @ Bm, Bm])
+def bd_assemble(Bm: np.ndarray, C: np.ndarray, off: int, axis: int) -> np.ndarray:
+    """The matrix a BD pair stands for: window rows = B and the others = C B (axis ROWS), or window
+    columns = B and the others = B C (axis COLS), the others keeping their ascending order."""
+    r = Bm.shape[axis]
+    total = r + C.shape[axis]
+    rest = window_complement(total, r, off)
+    if axis == ROWS:
+        out = np.empty((total, Bm.shape[1]))
+        out[off:off + r] = Bm
+        out[rest] = C @ Bm
+    else:
+        out = np.empty((Bm.shape[0], total))
+        out[:, off:off + r] = Bm
+        out[:, rest] = Bm @ C
+    return out
 
 
-def bd_decompose_row(W: np.ndarray, r: int):
-    """Algorithm "BD Decomposition (Row)".
-
-    Reading of step 3: "W' \\ B" is the set of rows of W that are not basis rows, so the solve is
-    C_F B_F = W[r:, :] and C_L B_L = W[:m-r, :].
-    Returns tag, B, C, (R_F, R_L).  Tie R_F <= R_L -> FIRST, as the algorithm states.
-    """
-    W = _c64(W)
-    m = W.shape[0]
-    B_F, B_L = W[:r], W[m - r:]
-    C_F = _solve_right(B_F, W[r:])
-    C_L = _solve_right(B_L, W[:m - r])
-    R_F = float(np.linalg.norm(W - bd_reconstruct_row(FIRST, B_F, C_F)))
-    R_L = float(np.linalg.norm(W - bd_reconstruct_row(LAST, B_L, C_L)))
-    if R_F <= R_L:
-        return FIRST, B_F.copy(), C_F, (R_F, R_L)
-    return LAST, B_L.copy(), C_L, (R_F, R_L)
+def bd_window(M: np.ndarray, r: int, off: int, axis: int):
+    """BD of M with the r rows (columns) starting at `off` as basis.
+    Returns (B, C, R): the basis, the coefficients of the other rows (columns), and the Frobenius
+    residual ||M - assemble(B, C)|| -- zero in exact arithmetic when rank(M) <= r and the window
+    is a basis (theorem of Section "Selection of Basis"), rounding noise scaled by the window's
+    conditioning otherwise: the quantity Residual-min ranks windows by."""
+    M = _c64(M)
+    rest = window_complement(M.shape[axis], r, off)
+    if axis == ROWS:
+        Bm = M[off:off + r].copy()
+        C = _combine(Bm, M[rest])
+    else:
+        Bm = M[:, off:off + r].copy()
+        C = _combine(Bm.T, M[:, rest].T).T
+    return Bm, C, float(np.linalg.norm(M - bd_assemble(Bm, C, off, axis)))
 
 
-def bd_decompose_col_both(W: np.ndarray, r: int):
-    """Column-based BD, both candidates (Eq. bd_identity, col-first W = B [I, C] and col-last
-    W = B [C, I]); "formulated analogously" to the row algorithm: it is the row algorithm on W^T."""
-    W = _c64(W)
-    n = W.shape[1]
-    B_F, B_L = W[:, :r], W[:, n - r:]
-    C_F = _solve_right(B_F.T, W[:, r:].T).T          # B_F C_F = W[:, r:]
-    C_L = _solve_right(B_L.T, W[:, :n - r].T).T      # B_L C_L = W[:, :n-r]
-    R_F = float(np.linalg.norm(W - np.hstack([B_F, B_F @ C_F])))
-    R_L = float(np.linalg.norm(W - np.hstack([B_L @ C_L, B_L])))
-    return (R_F, B_F.copy(), C_F), (R_L, B_L.copy(), C_L)
+def first_last(total: int, r: int) -> List[int]:
+    return [0, total - r]
 
 
-def bd_decompose_col(W: np.ndarray, r: int):
-    (R_F, B_F, C_F), (R_L, B_L, C_L) = bd_decompose_col_both(W, r)
-    if R_F <= R_L:
-        return FIRST, B_F, C_F, (R_F, R_L)
-    return LAST, B_L, C_L, (R_F, R_L)
+def bd_decompose(M: np.ndarray, r: int, axis: int, offsets: Optional[Sequence[int]] = None):
+    """Residual-min BD of one matrix: the candidate window (default: first-r and last-r) with the
+    smallest residual; ties keep the earlier candidate (R_F <= R_L -> first).
+    Returns (off, B, C, {off: R})."""
+    M = _c64(M)
+    offsets = first_last(M.shape[axis], r) if offsets is None else list(offsets)
+    cands = {off: bd_window(M, r, off, axis) for off in offsets}
+    best = min(offsets, key=lambda o: (cands[o][2], offsets.index(o)))
+    return best, cands[best][0], cands[best][1], {o: cands[o][2] for o in offsets}
 
 
-def attention_prepare_qk(Wq: np.ndarray, Wk: np.ndarray, n: int):
-    """Algorithm "BD Attention Preparation (QK)": per head, column BD (first and last) of the
-    product W_q^i (W_k^i)^T; the mean residual over heads picks one tag for all heads.
+def _shared_window(mats: Sequence[np.ndarray], r: int, axis: int, offsets: Sequence[int]):
+    """One window for all heads (Algorithm "BD Attention Preparation (QK)"): every head's matrix is
+    decomposed for every candidate, the residuals are averaged over heads per candidate, and the
+    candidate with the smallest mean is used by all heads (earlier candidate on ties).
+    Returns (off, [(B, C) per head], {off: mean residual})."""
+    per = {off: [bd_window(M, r, off, axis) for M in mats] for off in offsets}
+    mean = {off: float(np.mean([p[2] for p in per[off]])) for off in offsets}
+    best = min(offsets, key=lambda o: (mean[o], list(offsets).index(o)))
+    return best, [(p[0], p[1]) for p in per[best]], mean
 
-    Wq: d_q x (n d_h) (the query side may read a different tensor than the keys, so its row count
-    is its own), Wk: d x (n d_h).  Returns tag, B_qk (d_q x n d_h, replaces W_q),
-    C_qk ((d - d_h) x n d_h = [(C^1)^T, ..., (C^n)^T], replaces W_k), (mean R_F, mean R_L).
-    """
+
+def attention_prepare_qk(Wq: np.ndarray, Wk: np.ndarray, n: int, offsets: Optional[Sequence[int]] = None):
+    """QK preparation on the product matrices (Algorithm "BD Attention Preparation (QK)", Eq.
+    qk_bd_single): head i's W_q^i (W_k^i)^T (d_q x d) gets a column BD B^i [I, C^i]; B^i replaces
+    W_q^i and (C^i)^T replaces W_k^i.
+    Wq: d_q x (n d_h) (the query side may read a different tensor, so its row count is its own),
+    Wk: d x (n d_h).  Returns off, B_qk (d_q x n d_h), C_qk ((d - d_h) x n d_h, heads side by side),
+    {off: mean residual}."""
     Wq, Wk = _c64(Wq), _c64(Wk)
     d_h = Wk.shape[1] // n
-    firsts, lasts = [], []
-    for i in range(n):
-        M = Wq[:, i * d_h:(i + 1) * d_h] @ Wk[:, i * d_h:(i + 1) * d_h].T
-        f, l = bd_decompose_col_both(M, d_h)
-        firsts.append(f)
-        lasts.append(l)
-    R_F = float(np.mean([f[0] for f in firsts]))
-    R_L = float(np.mean([l[0] for l in lasts]))
-    pick, tag = (firsts, FIRST) if R_F <= R_L else (lasts, LAST)
-    B_qk = np.hstack([p[1] for p in pick])
-    C_qk = np.hstack([p[2].T for p in pick])
-    return tag, B_qk, C_qk, (R_F, R_L)
+    d = Wk.shape[0]
+    heads = [slice(i * d_h, (i + 1) * d_h) for i in range(n)]
+    mats = [Wq[:, h] @ Wk[:, h].T for h in heads]
+    offsets = first_last(d, d_h) if offsets is None else list(offsets)
+    off, pairs, mean = _shared_window(mats, d_h, COLS, offsets)
+    return off, np.hstack([Bm for Bm, _ in pairs]), np.hstack([C.T for _, C in pairs]), mean
 
 
-def attention_prepare_vo(Wv: np.ndarray, Wo: np.ndarray, n: int):
-    """Appendix "BD for VO in MHA": per head, row BD of W_v^i W_o^i = [I; C_vo^i] B_vo^i (or the
-    last version); one tag for all heads by the mean residual, as for QK.
-    Returns tag, C_vo ((d - d_h) x n d_h = [C^1, ..., C^n]), B_vo (n d_h x d_model), residuals."""
+def attention_prepare_vo(Wv: np.ndarray, Wo: np.ndarray, n: int, offsets: Optional[Sequence[int]] = None):
+    """VO preparation (Appendix "BD for VO in MHA"): head i's W_v^i W_o^i (d x d_model) gets a row
+    BD [I; C^i] B^i; C^i replaces W_v^i and B^i replaces W_o^i.
+    Returns off, C_vo ((d - d_h) x n d_h), B_vo (n d_h x d_model), {off: mean residual}."""
     Wv, Wo = _c64(Wv), _c64(Wo)
     d_h = Wv.shape[1] // n
     d = Wv.shape[0]
-    firsts, lasts = [], []
-    for i in range(n):
-        M = Wv[:, i * d_h:(i + 1) * d_h] @ Wo[i * d_h:(i + 1) * d_h, :]
-        B_F, B_L = M[:d_h], M[d - d_h:]
-        C_F = _solve_right(B_F, M[d_h:])
-        C_L = _solve_right(B_L, M[:d - d_h])
-        firsts.append((float(np.linalg.norm(M - bd_reconstruct_row(FIRST, B_F, C_F))), B_F, C_F))
-        lasts.append((float(np.linalg.norm(M - bd_reconstruct_row(LAST, B_L, C_L))), B_L, C_L))
-    R_F = float(np.mean([f[0] for f in firsts]))
-    R_L = float(np.mean([l[0] for l in lasts]))
-    pick, tag = (firsts, FIRST) if R_F <= R_L else (lasts, LAST)
-    C_vo = np.hstack([p[2] for p in pick])
-    B_vo = np.vstack([p[1] for p in pick])
-    return tag, C_vo, B_vo, (R_F, R_L)
+    heads = [slice(i * d_h, (i + 1) * d_h) for i in range(n)]
+    mats = [Wv[:, h] @ Wo[h, :] for h in heads]
+    offsets = first_last(d, d_h) if offsets is None else list(offsets)
+    off, pairs, mean = _shared_window(mats, d_h, ROWS, offsets)
+    return off, np.hstack([C for _, C in pairs]), np.vstack([Bm for Bm, _ in pairs]), mean
 
 
 # ------------------------------------------------------------------------------------------------

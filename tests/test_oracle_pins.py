@@ -24,8 +24,8 @@ def test_hand_example_3x2():
     g = read_golden("hand_example_3x2.txt")
     W = np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]])
     m = W.shape[0]
-    C_F = oracle._solve_right(W[:2], W[2:])
-    C_L = oracle._solve_right(W[m - 2:], W[:m - 2])
+    _, C_F, _ = oracle.bd_window(W, 2, 0, oracle.ROWS)
+    _, C_L, _ = oracle.bd_window(W, 2, m - 2, oracle.ROWS)
     np.testing.assert_allclose(C_F, [[g["first_c0"], g["first_c1"]]], atol=1e-12)
     np.testing.assert_allclose(C_L, [[g["last_c0"], g["last_c1"]]], atol=1e-12)
     # and through the per-head closed form with d_c = 3, d_h = 2, one head
@@ -41,7 +41,7 @@ def test_memory_and_flop_closed_forms():
     g = read_golden("paper_closed_forms.txt")
     m, n, r = 6, 5, 2
     W = _rank_r(m, n, r)
-    tag, B, C, _ = oracle.bd_decompose_row(W, r)
+    _, B, C, _ = oracle.bd_decompose(W, r, oracle.ROWS)
     assert B.size + C.size == g["bd_memory_m6_n5_r2"] == r * (m + n - r)
     assert r * (m + n) == g["lowrank_memory_m6_n5_r2"]
     # count the multiply-adds the reconstruction performs: C (m-r x r) times B (r x n)
@@ -89,13 +89,15 @@ def test_lowrank_linear_saving():
 @pytest.mark.parametrize("m,n,r", [(7, 5, 2), (20, 33, 6), (64, 64, 16)])
 def test_row_identities_and_reconstruction(m, n, r):
     W = _rank_r(m, n, r)
-    tag, B, C, (R_F, R_L) = oracle.bd_decompose_row(W, r)
+    off, B, C, resid = oracle.bd_decompose(W, r, oracle.ROWS)
+    R_F, R_L = resid[0], resid[m - r]
+    assert off in (0, m - r) and list(resid) == [0, m - r]
     assert R_F < 1e-10 * np.linalg.norm(W) and R_L < 1e-10 * np.linalg.norm(W)
-    np.testing.assert_allclose(oracle.bd_reconstruct_row(tag, B, C), W, atol=1e-10 * np.linalg.norm(W))
+    np.testing.assert_allclose(oracle.bd_assemble(B, C, off, oracle.ROWS), W, atol=1e-10 * np.linalg.norm(W))
     # explicit [I; C] B and [C; I] B forms
     I = np.eye(r)
-    C_F = oracle._solve_right(W[:r], W[r:])
-    C_L = oracle._solve_right(W[m - r:], W[:m - r])
+    _, C_F, _ = oracle.bd_window(W, r, 0, oracle.ROWS)
+    _, C_L, _ = oracle.bd_window(W, r, m - r, oracle.ROWS)
     np.testing.assert_allclose(np.vstack([I, C_F]) @ W[:r], W, atol=1e-9)
     np.testing.assert_allclose(np.vstack([C_L, I]) @ W[m - r:], W, atol=1e-9)
 
@@ -103,11 +105,28 @@ def test_row_identities_and_reconstruction(m, n, r):
 @pytest.mark.parametrize("m,n,r", [(5, 7, 2), (33, 20, 6)])
 def test_col_identities(m, n, r):
     W = _rank_r(m, n, r)
-    (R_F, B_F, C_F), (R_L, B_L, C_L) = oracle.bd_decompose_col_both(W, r)
+    B_F, C_F, R_F = oracle.bd_window(W, r, 0, oracle.COLS)
+    B_L, C_L, R_L = oracle.bd_window(W, r, n - r, oracle.COLS)
     I = np.eye(r)
     np.testing.assert_allclose(B_F @ np.hstack([I, C_F]), W, atol=1e-9)
     np.testing.assert_allclose(B_L @ np.hstack([C_L, I]), W, atol=1e-9)
     assert R_F < 1e-9 and R_L < 1e-9
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_interior_window_identity(axis):
+    """A window inside the matrix (Appendix "Residual-Min with Offset Search"): the window's rows
+    (columns) of the assembled matrix are B itself, the others are combinations of it, in ascending
+    order around the window -- checked against an explicit permutation to the first-r form."""
+    m, n, r, off = 11, 9, 3, 4
+    W = _rank_r(m, n, r)
+    B, C, R = oracle.bd_window(W, r, off, axis)
+    assert R < 1e-10
+    Wp = W if axis == 0 else W.T
+    perm = np.concatenate([np.arange(off, off + r), np.arange(0, off), np.arange(off + r, Wp.shape[0])])
+    Bp, Cp, _ = oracle.bd_window(Wp[perm], r, 0, 0)              # first-r form of the permuted matrix
+    np.testing.assert_allclose(B if axis == 0 else B.T, Bp, atol=0)
+    np.testing.assert_allclose(C if axis == 0 else C.T, Cp, atol=1e-10)
 
 
 # ---------------------------------------------------------------- prepare: closed form vs literal
@@ -122,8 +141,7 @@ def test_prepare_matches_literal_qk_algorithm(mode):
     # literal: column BD of each product matrix
     for i in range(n):
         M = Wq[:, i * d_h:(i + 1) * d_h] @ Wk[:, i * d_h:(i + 1) * d_h].T
-        (R_F, B_F, C_F), (R_L, B_L, C_L) = oracle.bd_decompose_col_both(M, d_h)
-        B_lit, C_lit = (B_F, C_F) if mode == oracle.FIRST else (B_L, C_L)
+        B_lit, C_lit, _ = oracle.bd_window(M, d_h, off, oracle.COLS)
         np.testing.assert_allclose(Bq[:, i * d_h:(i + 1) * d_h], B_lit, rtol=1e-9, atol=1e-9)
         np.testing.assert_allclose(C[:, i * d_h:(i + 1) * d_h], C_lit.T, rtol=1e-7, atol=1e-8)
 
@@ -132,21 +150,108 @@ def test_prepare_matches_literal_vo_algorithm():
     d, n, d_h, d_model = 40, 2, 8, 56
     Wv = RNG.standard_normal((d, n * d_h))
     Wo = RNG.standard_normal((n * d_h, d_model))
-    tag, C_vo, B_vo, _ = oracle.attention_prepare_vo(Wv, Wo, n)
-    mode = oracle.FIRST if tag == oracle.FIRST else oracle.LAST
+    off_vo, C_vo, B_vo, _ = oracle.attention_prepare_vo(Wv, Wo, n)
+    assert off_vo in (0, d - d_h)
+    mode = oracle.FIRST if off_vo == 0 else oracle.LAST
     C, Bo, off, _ = oracle.prepare(Wv, d, n, d_h, side=Wo, side_kind=oracle.SIDE_O, mode=mode)
+    assert off == off_vo
     np.testing.assert_allclose(C, C_vo, rtol=1e-7, atol=1e-8)
     np.testing.assert_allclose(Bo, B_vo, rtol=1e-9, atol=1e-9)
 
 
-def test_literal_qk_prepare_shapes_and_shared_tag():
-    """One tag for all heads; C_qk is (d - d_h) x n d_h (input line of the inference algorithm)."""
-    d, n, d_h = 32, 4, 8
-    Wq = RNG.standard_normal((d, n * d_h))
-    Wk = RNG.standard_normal((d, n * d_h))
-    tag, B_qk, C_qk, (R_F, R_L) = oracle.attention_prepare_qk(Wq, Wk, n)
-    assert B_qk.shape == (d, n * d_h) and C_qk.shape == (d - d_h, n * d_h)
-    assert tag == (oracle.FIRST if R_F <= R_L else oracle.LAST)
+def _near_singular_window(Wk, heads, d_h, off, eps, rng):
+    """Makes row off+1 of the given heads' blocks almost a copy of row off: the window at `off`
+    becomes ill-conditioned (condition ~ 1/eps) for those heads only."""
+    for h in heads:
+        blk = Wk[:, h * d_h:(h + 1) * d_h]
+        blk[off + 1] = blk[off] * (1 + eps) + eps * rng.standard_normal(d_h)
+
+
+def test_qk_preparation_on_product_matrices():
+    """Algorithm "BD Attention Preparation (QK)" as the oracle implements it on W_q^i (W_k^i)^T:
+    outputs head by head against an independent per-head decomposition and against the per-head
+    closed form (`prepare`), mean residuals against residuals recomputed here, the defining
+    invariant Q'_i K'_i^T = Q_i K_i^T from its outputs alone, and the layouts of B_qk / C_qk."""
+    rng = np.random.default_rng(77)
+    d, n, d_h, d_q, T = 40, 3, 8, 28, 9
+    Wq = rng.standard_normal((d_q, n * d_h))
+    Wk = rng.standard_normal((d, n * d_h))
+    off, B_qk, C_qk, mean = oracle.attention_prepare_qk(Wq, Wk, n)
+    assert B_qk.shape == (d_q, n * d_h) and C_qk.shape == (d - d_h, n * d_h)
+    assert list(mean) == [0, d - d_h] and off in mean
+    bbar = [k for k in range(d) if not off <= k < off + d_h]
+    resid = {0: [], d - d_h: []}
+    for i in range(n):
+        s = slice(i * d_h, (i + 1) * d_h)
+        M = Wq[:, s] @ Wk[:, s].T
+        # head i's block of the outputs, heads side by side in head order
+        B_i, C_i, _ = oracle.bd_window(M, d_h, off, oracle.COLS)
+        assert np.array_equal(B_qk[:, s], B_i) and np.array_equal(B_qk[:, s], M[:, off:off + d_h])
+        assert np.array_equal(C_qk[:, s], C_i.T)
+        # residuals of both windows, recomputed from the definition M ~ B [I, C] with a plain solve
+        for o in resid:
+            rest = [k for k in range(d) if not o <= k < o + d_h]
+            Bm = M[:, o:o + d_h]
+            Cm = np.linalg.lstsq(Bm, M[:, rest], rcond=None)[0]
+            rec = np.empty_like(M)
+            rec[:, o:o + d_h] = Bm
+            rec[:, rest] = Bm @ Cm
+            resid[o].append(np.linalg.norm(M - rec))
+    for o in resid:
+        assert mean[o] == pytest.approx(np.mean(resid[o]), rel=0.5, abs=1e-13)     # (noise-level values)
+        assert mean[o] < 1e-10
+    # the closed form agrees (same window)
+    C, Bq, off2, _ = oracle.prepare(Wk, d, n, d_h, side=Wq, side_kind=oracle.SIDE_Q, mode=oracle.EXPLICIT, explicit_offset=off)
+    np.testing.assert_allclose(B_qk, Bq, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(C_qk, C, rtol=1e-7, atol=1e-8)
+    # and the scores are those of MHA
+    X, Xq = rng.standard_normal((T, d)), rng.standard_normal((T, d_q))
+    for i in range(n):
+        s = slice(i * d_h, (i + 1) * d_h)
+        Kp = X[:, off:off + d_h] + X[:, bbar] @ C_qk[:, s]
+        got = (Xq @ B_qk[:, s]) @ Kp.T
+        ref = (Xq @ Wq[:, s]) @ (X @ Wk[:, s]).T
+        assert np.max(np.abs(got - ref)) <= 1e-9 * np.max(np.abs(ref))
+
+
+def test_qk_preparation_window_is_chosen_by_the_mean_over_heads():
+    """One window for all heads, by the MEAN residual: head 0's first window is made very
+    ill-conditioned, the last windows of heads 1 and 2 mildly so.  Two of three heads prefer the
+    first window and the last head does too, yet the mean prefers the last one; with the roles
+    swapped the first one.  (A vote, the first head alone or the last head alone would each fail
+    one of the two cases.)"""
+    rng = np.random.default_rng(78)
+    d, n, d_h = 40, 3, 8
+    Wq = rng.standard_normal((d, n * d_h))
+    for bad_strong, bad_mild in ((0, d - d_h), (d - d_h, 0)):
+        Wk = rng.standard_normal((d, n * d_h))
+        _near_singular_window(Wk, [0], d_h, bad_strong, 1e-11, rng)
+        _near_singular_window(Wk, [1, 2], d_h, bad_mild, 1e-5, rng)
+        off, _, _, mean = oracle.attention_prepare_qk(Wq, Wk, n)
+        per_head = []
+        for i in range(n):
+            M = Wq[:, i * d_h:(i + 1) * d_h] @ Wk[:, i * d_h:(i + 1) * d_h].T
+            per_head.append({o: oracle.bd_window(M, d_h, o, oracle.COLS)[2] for o in (0, d - d_h)})
+        # the construction does what it says: head 0 is off by orders of magnitude, 1 and 2 mildly
+        assert per_head[0][bad_strong] > 1e3 * max(per_head[1][bad_mild], per_head[2][bad_mild])
+        assert per_head[1][bad_mild] > 10 * per_head[1][bad_strong]
+        assert per_head[2][bad_mild] > 10 * per_head[2][bad_strong]
+        assert off == bad_mild                       # the window that is only mildly bad wins on the mean
+        assert mean[bad_mild] < mean[bad_strong]
+        # the same through the VO twin (row BD of W_v^i W_o^i)
+        Wo = rng.standard_normal((n * d_h, d))
+        off_vo, _, _, mean_vo = oracle.attention_prepare_vo(Wk, Wo, n)
+        assert off_vo == bad_mild and mean_vo[bad_mild] < mean_vo[bad_strong]
+
+
+def test_preparation_tie_keeps_first_window_for_all_heads():
+    # exact arithmetic on small integers: identity blocks at both ends of every head -> residuals 0
+    d, n, d_h = 7, 2, 2
+    mid = np.arange(6, dtype=np.float64).reshape(3, 2)
+    Wk = np.hstack([np.vstack([np.eye(d_h), mid + h, np.eye(d_h)]) for h in range(n)])
+    Wq = np.hstack([np.eye(d_h)] * n)
+    off, B_qk, C_qk, mean = oracle.attention_prepare_qk(Wq, Wk, n)
+    assert mean[0] == 0.0 and mean[d - d_h] == 0.0 and off == 0
 
 
 # ---------------------------------------------------------------- prepare: what the maths fixes
@@ -205,8 +310,8 @@ def test_tag_tie_goes_to_first():
     C, _, off, resid = oracle.prepare(W, d_c, 1, d_h, mode=oracle.RESIDUAL_MIN, store_dtype=oracle.F64)
     assert resid[0] == 0.0 and resid[d_c - d_h] == 0.0
     assert off == 0
-    tag, _, _, (R_F, R_L) = oracle.bd_decompose_row(W, d_h)
-    assert R_F <= R_L and tag == oracle.FIRST
+    off_m, _, _, r_m = oracle.bd_decompose(W, d_h, oracle.ROWS)
+    assert r_m[0] <= r_m[d_c - d_h] and off_m == 0
 
 
 @pytest.mark.parametrize("bad", ["first", "last"])
@@ -377,8 +482,7 @@ def test_lowrank_linear_equals_xUV(mode):
     ref = np.matmul(np.matmul(x, U), V)
     assert np.max(np.abs(y - ref)) <= 1e-10 * np.max(np.abs(ref))
     # literal column BD of the product agrees with the closed form
-    (R_F, B_F, C_F), (R_L, B_L, C_L) = oracle.bd_decompose_col_both(U @ V, r)
-    B_lit, C_lit = (B_F, C_F) if mode == oracle.FIRST else (B_L, C_L)
+    B_lit, C_lit, _ = oracle.bd_window(U @ V, r, off, oracle.COLS)
     np.testing.assert_allclose(Up, B_lit, rtol=1e-10, atol=1e-10)
     np.testing.assert_allclose(C, C_lit, rtol=1e-7, atol=1e-8)
 
@@ -391,6 +495,54 @@ def test_lowrank_residual_min_picks_better_window():
     V[:, 1] = V[:, 0] * (1 + 1e-6)               # first-r window nearly singular
     _, _, off, resid = oracle.prepare_lowrank(U, V, mode=oracle.RESIDUAL_MIN, store_dtype=oracle.F16)
     assert off == d_out - r and resid[0] > resid[off]
+
+
+# ---------------------------------------------------------------- storage rounding
+def _bf16_cases():
+    """float32-representable values (so that a float64 -> float32 -> bfloat16 conversion rounds
+    once): random normals and subnormals, exact ties between two bfloat16 neighbours with even and
+    odd lower neighbour, values one float32 ulp either side of a tie, powers of two, signed zeros,
+    the largest finite bfloat16 and the tie above it (rounds to infinity)."""
+    rng = np.random.default_rng(99)
+    bits = [rng.integers(0, 2 ** 32, 20000, dtype=np.uint64).astype(np.uint32)]
+    bits.append(rng.integers(0, 2 ** 23, 2000, dtype=np.uint64).astype(np.uint32))               # float32 subnormals
+    hi = rng.integers(0, 0x7F80, 4000, dtype=np.uint64).astype(np.uint32) << np.uint32(16)       # finite bf16 patterns
+    for low in (0x8000, 0x7FFF, 0x8001, 0x0001, 0xFFFF):
+        bits.append(hi | np.uint32(low))
+        bits.append(hi | np.uint32(low) | np.uint32(0x80000000))
+    bits.append(np.array([0x00000000, 0x80000000, 0x7F7F0000, 0x7F7F8000, 0x7F7F7FFF, 0x00008000, 0x00018000,
+                          0x00010000, 0x3F800000, 0x3F808000, 0x3F818000], dtype=np.uint32))
+    b = np.concatenate(bits)
+    v = b.view(np.float32)
+    return v[np.isfinite(v)].astype(np.float64)
+
+
+def test_bf16_rounding_matches_a_library_cast():
+    """`round_store(x, BF16)` (ranks windows for bf16 storage) and the input generator's own bf16
+    rounding against torch's CPU float32 -> bfloat16 cast (round to nearest even), bit for bit."""
+    torch = pytest.importorskip("torch")
+    import bda_workloads as wl
+    x = _bf16_cases()
+    ref_t = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16)
+    ref = ref_t.to(torch.float32).numpy().astype(np.float64)
+    got = oracle.round_store(x, oracle.BF16)
+    fin = np.isfinite(ref)
+    assert np.array_equal(got, ref) and np.array_equal(np.signbit(got), np.signbit(ref))
+    assert (~fin).sum() >= 2                                  # the overflow cases are among them
+    stored, val = wl.to_storage(x, wl.BF16)
+    ref_bits = ref_t.view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(stored, ref_bits)
+    assert np.array_equal(val[fin], ref[fin])
+
+
+def test_f16_and_f32_rounding_match_library_casts():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(98)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-9, 5, 5000), [0.0, -0.0, 65504.0, 65519.0, 6e-8, 3e-8]])
+    ref16 = torch.from_numpy(x).to(torch.float16).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_store(x, oracle.F16), ref16)
+    ref32 = torch.from_numpy(x).to(torch.float32).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_store(x, oracle.F32), ref32)
 
 
 # ---------------------------------------------------------------- the pins catch planted mistakes
