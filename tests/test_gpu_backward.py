@@ -137,6 +137,44 @@ def test_backward_benchmark_shape_full():
     _check(4096, 512, 128, [16, 16], [0, 0], wl.F16, what="v2lite")
 
 
+def test_backward_v3_shape_sampled():
+    """The V3-shaped training step (T = 8192, 128 + 128 heads, bf16, two different windows), the
+    shape the largest forward configuration has: grad_c on 264 sampled token rows (its rows are
+    independent, so the oracle computes exactly those), grad_C on 10 sampled heads (all tokens, all
+    rows of C; the oracle is given the reduced problem made of those heads' columns).  Gradients
+    start as NaN patterns and must be finite everywhere."""
+    T, d_c, d_h, H, offs, dtype = 8192, 512, 128, [128, 128], [0, 384], wl.BF16
+    N, K = sum(H) * d_h, d_c - d_h
+    rng = np.random.default_rng([31, T, d_c])
+    c_s, c64 = wl.to_storage(rng.standard_normal((T, d_c)), dtype)
+    C_s, C64 = wl.to_storage(0.25 * rng.standard_normal((K, N)), dtype)
+    g_s = np.empty((T, N), dtype=np.uint16)
+    for r0 in range(0, T, 512):                                   # chunked: the float64 draw of the whole matrix is 2 GiB
+        g_s[r0:r0 + 512], _ = wl.to_storage(rng.standard_normal((512, N)), dtype)
+    c_d, g_d, C_d = gh.to_device(c_s, dtype), gh.to_device(g_s, dtype), gh.to_device(C_s, dtype)
+    gc_d = gh.new_out(T, d_c, dtype, fill=0x7FC0)
+    gC_d = gh.new_out(K, N, dtype, fill=0x7FC0)
+    bda.bda_kv_project_backward(c_d, d_c, g_d, N, C_d, N, T, d_c, d_h, H, offs, gc_d, d_c, gC_d, N, dtype, dtype, gh.stream())
+    torch.cuda.synchronize()
+    gc, gC = gh.to_host64(gc_d, dtype), gh.to_host64(gC_d, dtype)
+    assert np.all(np.isfinite(gc)) and np.all(np.isfinite(gC))
+    # grad_c: first / last rows, one row per 128-token tile, random rows
+    rows = set(range(4)) | set(range(T - 4, T)) | {128 * b + (37 * b + 5) % 128 for b in range(T // 128)}
+    rows |= set(int(r) for r in rng.integers(0, T, 192))
+    rows = np.array(sorted(rows))
+    assert len(rows) >= 256
+    ref_c, _ = oracle.kv_project_backward(c64[rows], wl.from_storage(g_s[rows], dtype), C64, d_h, H, offs)
+    rel_c = assert_parity(gc[rows], ref_c, 1, dtype, dtype, "v3 grad_c, sampled rows")
+    # grad_C: sampled heads of both groups
+    heads = sorted({0, 1, 127, 128, 129, 255} | set(int(h) for h in rng.integers(0, 256, 4)))
+    cols = np.concatenate([np.arange(h * d_h, (h + 1) * d_h) for h in heads])
+    H_sub = [sum(1 for h in heads if h < 128), sum(1 for h in heads if h >= 128)]
+    g_sub = wl.from_storage(np.ascontiguousarray(g_s[:, cols]), dtype)
+    _, ref_C = oracle.kv_project_backward(c64, g_sub, C64[:, cols], d_h, H_sub, offs)
+    rel_C = assert_parity(gC[:, cols], ref_C, 1, dtype, dtype, "v3 grad_C, sampled heads")
+    print(f"v3 backward: grad_c {len(rows)} rows {rel_c:.2e}; grad_C {len(heads)} heads {rel_C:.2e}")
+
+
 @pytest.mark.parametrize("seed", [1, 2])
 def test_backward_random_shapes(seed):
     """Seeded random shapes (head widths 32 .. 128 incl. 96, contraction 32 .. 448 in steps of 8 with

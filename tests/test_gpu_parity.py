@@ -6,7 +6,7 @@ import pytest
 
 import bda_workloads as wl
 import oracle
-from helpers import assert_parity, lowrank_h_rounding_allowance
+from helpers import assert_parity, lowrank_h_rounding_allowance, parity_error
 
 pytestmark = pytest.mark.gpu
 
@@ -444,56 +444,156 @@ def test_lowrank_linear_small(last, dtype):
     extra = lowrank_h_rounding_allowance(ref, C64, lw.r, off, dtype)
     assert_parity(got, ref, lw.d_out, dtype, dtype, "lowrank", extra)
     assert_parity(got[:, off:off + lw.r], ref[:, off:off + lw.r], lw.r, dtype, dtype, "lowrank h block")
+    # the second product alone, from the h the GPU stored, at the plain tolerance
+    rest = np.concatenate([np.arange(0, off), np.arange(off + lw.r, lw.d_out)])
+    ref2 = oracle.dense_project(got[:, off:off + lw.r], C64)
+    assert_parity(got[:, rest], ref2, lw.d_out - lw.r, dtype, dtype, "lowrank h C from the stored h")
 
 
 # ------------------------------------------------------------------------------------ full benchmark sizes
-def _sample_rows(T, n_random, seed):
+NAN_FILL = {wl.F16: float("nan"), wl.F32: float("nan"), wl.BF16: 0x7FC0}     # bf16 buffers are int16 bit patterns
+
+
+def _sample_rows(T, n_random, seed, block=32):
+    """First and last rows, the rows around the first 256-row tile border, one row inside every
+    `block`-row MFMA block of every token tile (its position inside the block varies), and
+    `n_random` random rows."""
     rng = np.random.default_rng(seed)
     rows = set(range(0, min(T, 4))) | set(range(max(T - 4, 0), T))
     rows |= {255, 256, 257} & set(range(T))
+    rows |= {min(T - 1, b * block + (7 * b + 3) % block) for b in range((T + block - 1) // block)}
     rows |= set(int(r) for r in rng.integers(0, T, n_random))
     return np.array(sorted(rows), dtype=np.int64)
 
 
-@pytest.mark.parametrize("name,n_rows", [("v2lite", 96), ("v3", 48)])
-def test_full_size_configs_on_sampled_rows(name, n_rows):
-    """Configs 2 and 4 in the launch configuration the bench times; the oracle computes the sampled
-    token rows (first and last tile, tile borders, random rows) for every head."""
-    w = wl.kv_workload(name)
+def _whole_output_check(got, c64, C64, d_h, H, offs, in_dtype, out_dtype, what, chunk=1024):
+    """Every element of a full-size output against a float64 numpy product of the same stored inputs
+    (tile(c[:, B]) + c[:, Bbar] @ C per group, a library GEMM -- not the oracle's loops, which
+    check the sampled rows), chunk by chunk; with the output pre-filled with NaN this also shows a
+    tile that was skipped."""
+    assert np.all(np.isfinite(got)), f"{what}: output holds NaN / inf (an unwritten or doubly damaged tile)"
+    d_c = c64.shape[1]
+    worst = 0.0
+    for r0 in range(0, c64.shape[0], chunk):
+        cc = c64[r0:r0 + chunk]
+        parts, col = [], 0
+        for Hg, off in zip(H, offs):
+            bbar = np.concatenate([np.arange(0, off), np.arange(off + d_h, d_c)])
+            w = Hg * d_h
+            parts.append(np.tile(cc[:, off:off + d_h], (1, Hg)) + np.matmul(cc[:, bbar], C64[:, col:col + w]))
+            col += w
+        ref = np.hstack(parts)
+        worst = max(worst, assert_parity(got[r0:r0 + chunk], ref, d_h, in_dtype, out_dtype, f"{what} rows {r0}.."))
+    return worst
+
+
+def test_full_size_config2_every_element():
+    """Config 2 (V2-Lite shape, T = 4096, fp16) in the launch configuration the bench times: every
+    element against the oracle's loops; the output starts as NaN."""
+    w = wl.kv_workload("v2lite")
     offs = [0, 0]
     C_stored, C64 = _prepare_stored(w.W, w.d_c, w.H, w.d_h, offs, w.dtype)
-    rows = _sample_rows(w.T, n_rows, seed=5)
-    ref = oracle.kv_project(w.c[rows], C64, w.d_h, w.H, offs)
-    got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype)
+    ref = oracle.kv_project(w.c, C64, w.d_h, w.H, offs)
+    got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, fill=NAN_FILL[w.dtype])
     assert np.all(np.isfinite(got))
-    # RMS floor from the sampled rows of each head (the full-output RMS is not available)
-    assert_parity(got[rows], ref, w.d_h, w.dtype, w.dtype, name)
-    if w.dtype == wl.BF16:
-        got32, _ = gh.kv_project(w.c_stored[:512], C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, out_dtype=wl.F32)
-        ref32 = oracle.kv_project(w.c[:64], C64, w.d_h, w.H, offs)
-        assert_parity(got32[:64], ref32, w.d_h, w.dtype, wl.F32, name + " fp32 out")
+    rel = assert_parity(got, ref, w.d_h, w.dtype, w.dtype, "v2lite, all rows")
+    print(f"config 2: max relative error {rel:.2e} over {got.size} elements")
 
 
-def test_full_size_lowrank_on_sampled_rows():
+def test_full_size_config4_sampled_rows_and_whole_output():
+    """Config 4 (V3 shape, T = 8192, bf16): the oracle's loops on 256 random rows plus one row in
+    every 32-row block of every token tile plus the borders (about 500 rows, all 32768 columns),
+    and every element against a float64 library GEMM; the output starts as NaN.  The same kernel
+    with float32 outputs is held to the plain tolerance on the first rows."""
+    w = wl.kv_workload("v3")
+    offs = [0, 0]
+    C_stored, C64 = _prepare_stored(w.W, w.d_c, w.H, w.d_h, offs, w.dtype)
+    rows = _sample_rows(w.T, 256, seed=5)
+    assert len(rows) >= 256 + w.T // 32 - 40
+    ref = oracle.kv_project(w.c[rows], C64, w.d_h, w.H, offs)
+    got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, fill=NAN_FILL[w.dtype])
+    rel = assert_parity(got[rows], ref, w.d_h, w.dtype, w.dtype, "v3 sampled rows")
+    worst = _whole_output_check(got, w.c, C64, w.d_h, w.H, offs, w.dtype, w.dtype, "v3 whole output")
+    print(f"config 4: {len(rows)} oracle rows, max relative error {rel:.2e}; whole output {worst:.2e}")
+    got32, _ = gh.kv_project(w.c_stored[:512], C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, out_dtype=wl.F32,
+                             fill=NAN_FILL[wl.F32])
+    ref32 = oracle.kv_project(w.c[:64], C64, w.d_h, w.H, offs)
+    assert np.all(np.isfinite(got32))
+    assert_parity(got32[:64], ref32, w.d_h, w.dtype, wl.F32, "v3 fp32 out")
+
+
+def test_full_size_lowrank_sampled_rows_and_whole_output():
+    """Config 5 (BD linear layer, T = 8192, fp16).  Three checks (Section "BD for Linear Layer"):
+      1. end to end against the oracle, whose h = x U' is never rounded: the h block at the plain
+         tolerance, the h C block with the derived allowance for the library's one rounding of h;
+      2. the second product alone at the PLAIN tolerance: the oracle is fed the h the GPU stored
+         (read back from the output), so nothing but the product h C is compared;
+      3. every element of the output against float64 library GEMMs on the same stored inputs
+         (same two-stage form as 2), the output starting as NaN."""
     lw = wl.lowrank_workload()
-    Up, C, off, _ = bda_prepare_lowrank_oracle(lw)
+    Up, C, off, _ = oracle.prepare_lowrank(lw.U, lw.V, mode=oracle.FIRST)
     Up_s, Up64 = wl.to_storage(Up, lw.dtype)
     C_s, C64 = wl.to_storage(C, lw.dtype)
-    rows = _sample_rows(lw.T, 24, seed=6)
-    ref = oracle.lowrank_linear(lw.x[rows], Up64, C64, off)
+    rows = _sample_rows(lw.T, 256, seed=6, block=256)
+    assert len(rows) >= 256
     x_d, U_d, C_d = gh.to_device(lw.x_stored, lw.dtype), gh.to_device(Up_s, lw.dtype), gh.to_device(C_s, lw.dtype)
-    out_d = gh.new_out(lw.T, lw.d_out, lw.dtype)
+    out_d = gh.new_out(lw.T, lw.d_out, lw.dtype, fill=NAN_FILL[lw.dtype])
     bda.bda_lowrank_linear(x_d, lw.d_in, lw.T, lw.d_in, lw.r, lw.d_out, off, U_d, C_d, out_d,
                            lw.d_out, lw.dtype, gh.stream())
     torch.cuda.synchronize()
     got = gh.to_host64(out_d, lw.dtype)
-    extra = lowrank_h_rounding_allowance(ref, C64, lw.r, off, lw.dtype)
-    assert_parity(got[rows], ref, lw.d_out, lw.dtype, lw.dtype, "lowrank full", extra)
-    assert_parity(got[rows][:, :lw.r], ref[:, :lw.r], lw.r, lw.dtype, lw.dtype, "lowrank full h block")
+    assert np.all(np.isfinite(got))
+    r = lw.r
+    # 1. end to end
+    ref = oracle.lowrank_linear(lw.x[rows], Up64, C64, off)
+    extra = lowrank_h_rounding_allowance(ref, C64, r, off, lw.dtype)
+    worst_e2e, _ = parity_error(got[rows], ref, lw.d_out, lw.dtype, lw.dtype, extra)
+    assert worst_e2e <= 1.0, worst_e2e
+    assert_parity(got[rows][:, :r], ref[:, :r], r, lw.dtype, lw.dtype, "lowrank full h block")
+    # 2. second product from the GPU's own stored h, plain tolerance
+    h_gpu = got[rows][:, :r]
+    ref2 = oracle.dense_project(h_gpu, C64)
+    rel2 = assert_parity(got[rows][:, r:], ref2, lw.d_out - r, lw.dtype, lw.dtype, "lowrank h C from the stored h")
+    # 3. whole output
+    worst = 0.0
+    for r0 in range(0, lw.T, 1024):
+        h_ref = np.matmul(lw.x[r0:r0 + 1024], Up64)
+        worst = max(worst, assert_parity(got[r0:r0 + 1024, :r], h_ref, r, lw.dtype, lw.dtype, f"lowrank h rows {r0}.."))
+        hc_ref = np.matmul(got[r0:r0 + 1024, :r], C64)
+        worst = max(worst, assert_parity(got[r0:r0 + 1024, r:], hc_ref, lw.d_out - r, lw.dtype, lw.dtype, f"lowrank h C rows {r0}.."))
+    print(f"config 5: {len(rows)} oracle rows; end-to-end worst ratio to its allowance {worst_e2e:.3f}; "
+          f"h C from the stored h {rel2:.2e}; whole output {worst:.2e}")
 
 
-def bda_prepare_lowrank_oracle(lw):
-    return oracle.prepare_lowrank(lw.U, lw.V, mode=oracle.FIRST)
+# ------------------------------------------------------------------------------------ rows past T
+@pytest.mark.parametrize("T,d_c,d_h,H,offs,dtype,policy,kernel", [
+    (5, 512, 128, [2, 1], [8, 384], wl.F16, 0, "decode32"),
+    (40, 512, 128, [2, 1], [8, 384], wl.BF16, 0, "decode32x2"),
+    (100, 512, 128, [2, 1], [8, 384], wl.F16, 0, "decode32x4"),
+    (20, 512, 128, [2, 1], [8, 384], wl.F16, 5, "decode128"),
+    (100, 512, 128, [2, 1], [8, 384], wl.BF16, 5, "decode64"),
+    (200, 512, 128, [3, 2], [72, 384], wl.F16, 0, "decode32 token tiles"),
+    (300, 512, 128, [4, 2], [64, 192], wl.F16, 1, "mfma128"),
+    (300, 512, 128, [4, 2], [64, 192], wl.BF16, 2, "lean256"),
+    (300, 512, 128, [4, 2], [64, 192], wl.F16, 3, "stream256"),
+    (300, 512, 128, [4, 2], [64, 192], wl.BF16, 4, "lean128"),
+    (77, 52, 20, [2, 3], [3, 32], wl.F16, 0, "general"),
+    (64, 64, 16, [2], [0], wl.F32, 0, "general fp32"),
+])
+def test_rows_past_T_are_not_written(T, d_c, d_h, H, offs, dtype, policy, kernel):
+    """Every kernel family with 40 poisoned rows after the last token and padded row pitches: the
+    result is right and neither the rows past T nor the columns past N are touched."""
+    w = wl.custom_kv_workload("guard", T=T, d_c=d_c, d_h=d_h, H=H, std=0.05, rms_norm=True, dtype=dtype, seed=90 + T)
+    C_stored, C64 = _prepare_stored(w.W, d_c, H, d_h, offs, dtype)
+    ref = oracle.kv_project(w.c, C64, d_h, H, offs)
+    N = w.N
+    poison = -7.0 if dtype != wl.BF16 else -7
+    got, raw = gh.kv_project(w.c_stored, C_stored, d_c, d_h, H, offs, dtype, ld_out=N + 8, fill=poison,
+                             policy=policy, extra_rows=40)
+    assert_parity(got, ref, d_h, dtype, dtype, kernel)
+    tail = raw[T:].cpu().numpy()
+    assert tail.shape[0] == 40 and np.all(tail == poison), f"{kernel}: rows past T were written"
+    assert np.all(raw[:T, N:].cpu().numpy() == poison), f"{kernel}: columns past N were written"
 
 
 # ------------------------------------------------------------------------------------ end to end
