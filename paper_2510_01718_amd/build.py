@@ -1,4 +1,5 @@
-"""Builds libbda.so (hipcc, gfx950) in-tree.  `python -m paper_2510_01718_amd.build`."""
+"""Builds libbda.so and the bench's libbda_yardsticks.so (hipcc, gfx950) in-tree.
+`python -m paper_2510_01718_amd.build`."""
 from __future__ import annotations
 
 import glob
@@ -9,6 +10,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB_PATH = os.path.join(PKG, "libbda.so")
+YARDSTICKS_PATH = os.path.join(PKG, "libbda_yardsticks.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -23,10 +25,7 @@ def sources():
     return sorted(glob.glob(os.path.join(c, "*.cpp")) + glob.glob(os.path.join(c, "*.hip")))
 
 
-def build(verbose: bool = False, extra=()) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"),
-           "-I", os.path.join(PKG, "csrc"), *sources(), "-o", LIB_PATH, "-lpthread"]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -36,8 +35,44 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    """libbda.so: every translation unit in csrc/ (one hipcc process per unit, in parallel)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    procs = []
+    objs = []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        objs.append(obj)
+        cmd = [hipcc, *compile_flags, *extra, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
+               "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for src, p in procs:
+        out, _ = p.communicate()
+        out = "\n".join(l for l in out.splitlines()
+                        if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n" + out)
+        if verbose and out.strip():
+            print(out)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH, "-lpthread"], verbose)
     return LIB_PATH
+
+
+def build_yardsticks(verbose: bool = False) -> str:
+    """libbda_yardsticks.so: the bench's reference kernels (empty launch, MFMA loop, streaming)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(PKG, "csrc", "yardsticks", "bda_yardsticks.hip")
+    _run([hipcc, *HIPCC_FLAGS, src, "-o", YARDSTICKS_PATH], verbose)
+    return YARDSTICKS_PATH
 
 
 if __name__ == "__main__":
     print(build(verbose=True, extra=sys.argv[1:]))
+    print(build_yardsticks(verbose=True))
