@@ -298,9 +298,9 @@ def main() -> int:
             yl = ctypes.CDLL(ypath)
             vp, ci, u64, u32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32
             yl.bdy_empty.argtypes = [ci, ci, vp]
-            yl.bdy_mfma_loop.argtypes = [ci, ci, ci, vp, vp]
+            yl.bdy_mfma_loop.argtypes = [ci, ci, ci, ci, vp, vp]
             yl.bdy_read.argtypes = [vp, u64, vp, ci, vp]
-            yl.bdy_write.argtypes = [vp, u64, u32, ci, vp]
+            yl.bdy_write.argtypes = [vp, u64, u32, ci, ci, vp]
             yl.bdy_copy.argtypes = [vp, vp, u64, ci, vp]
             sink = torch.zeros(64, dtype=torch.int32, device="cuda")
             y = {}
@@ -311,21 +311,25 @@ def main() -> int:
             y["empty_launch_256x512_us"] = bench_fixed(lambda i, s: ck(yl.bdy_empty(256, 512, s or None))) * 1e6
             y["empty_launch_1x64_loop_us"] = bench_fixed(lambda i, s: ck(yl.bdy_empty(1, 64, s or None)), graph=False) * 1e6
             it = 2000
-            for nm, bf in (("f16", 0), ("bf16", 1)):
-                t_m = bench_fixed(lambda i, s: ck(yl.bdy_mfma_loop(512, it, bf, sink.data_ptr(), s or None)))
-                y[f"mfma_loop_{nm}_tflops"] = 512 * 4 * it * 4 * 32768.0 / t_m / 1e12
+            for nm, bf in (("f16", 0), ("bf16", 1)):       # uniform operand values, then random ones (the board's power limit shows)
+                for rnd, sfx in ((0, ""), (1, "_random_data")):
+                    t_m = bench_fixed(lambda i, s: ck(yl.bdy_mfma_loop(512, it, bf, rnd, sink.data_ptr(), s or None)))
+                    y[f"mfma_loop_{nm}{sfx}_tflops"] = 512 * 4 * it * 4 * 32768.0 / t_m / 1e12
             big = 2 << 30                                      # 2 GiB: eight times the last-level cache
             src = torch.empty(big, dtype=torch.uint8, device="cuda").fill_(3)
             dst = torch.empty(big, dtype=torch.uint8, device="cuda")
             t_r = bench_fixed(lambda i, s: ck(yl.bdy_read(src.data_ptr(), big, sink.data_ptr(), 2048, s or None)))
-            t_w = bench_fixed(lambda i, s: ck(yl.bdy_write(dst.data_ptr(), big, 7, 2048, s or None)))
+            t_w = bench_fixed(lambda i, s: ck(yl.bdy_write(dst.data_ptr(), big, 7, 2048, 1, s or None)))
+            t_wp = bench_fixed(lambda i, s: ck(yl.bdy_write(dst.data_ptr(), big, 7, 2048, 0, s or None)))
             t_c = bench_fixed(lambda i, s: ck(yl.bdy_copy(src.data_ptr(), dst.data_ptr(), big, 2048, s or None)))
-            y["hbm_read_gbs"], y["hbm_write_gbs"] = big / t_r / 1e9, big / t_w / 1e9
+            y["hbm_read_gbs"], y["hbm_write_gbs"], y["hbm_write_plain_stores_gbs"] = big / t_r / 1e9, big / t_w / 1e9, big / t_wp / 1e9
             y["hbm_copy_gbs_read_plus_write"] = 2 * big / t_c / 1e9
             del src, dst
             extra["yardsticks"] = y
             log("yardsticks: " + ", ".join(f"{k} {v:.4g}" for k, v in y.items()))
             result["roofline"]["frac_of_measured_mfma_loop"] = result["roofline"]["achieved"] / y[f"mfma_loop_{wl.DTYPE_NAMES[w.dtype]}_tflops"]
+            result["roofline"]["frac_of_measured_mfma_loop_random_data"] = (
+                result["roofline"]["achieved"] / y[f"mfma_loop_{wl.DTYPE_NAMES[w.dtype]}_random_data_tflops"])
 
         # ---- dense comparator of the main workload, timed alternately with the BD launch
         W_stored, _ = wl.to_storage(w.W, w.dtype)

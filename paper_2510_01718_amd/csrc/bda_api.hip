@@ -88,7 +88,9 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
         const int64_t run = (tiles + kNumXcd - 1) / kNumXcd;                  // tiles per die
         const int slots = (int)std::min<int64_t>(kSlotsPerXcd, run);
         const int64_t lin_rounds = (run + slots - 1) / slots;
-        if (lin_rounds < a.rounds) {
+        // ... or as many, when the tile grid does not fill whole super-tiles (no idle slots inside a round then)
+        const bool ragged = a.m_tiles % a.sm != 0 || a.n_tiles % a.sn != 0;
+        if (lin_rounds < a.rounds || (lin_rounds == a.rounds && ragged)) {
             a.sm = a.sn = 1;
             a.n_super_m = a.m_tiles;
             a.n_super_n = a.n_tiles;
@@ -202,23 +204,38 @@ void build_tiles(GemmArgs& a, int G, const int64_t* group_cols, int bt, int bn)
     a.m_tiles = (int)((a.M + bt - 1) / bt);
 }
 
-// Shape of the block of tiles one die works on at a time: sm x sn = slots (workgroups per die), as
-// square as the tile grid allows, so that the die's L2 holds few distinct token and weight tiles.
-// A small tile grid gets fewer slots, so that there are at least as many super-tiles as dies and
-// every die (and its share of the memory channels) takes part.
-void choose_super(GemmArgs& a, int max_slots)
+// Shape of the block of tiles one die works on at a time: sm x sn = slots (workgroups per die).  A die
+// takes a contiguous run of super-tiles, numbered down the token dimension first, so within a run
+// every super-tile brings sm new token tiles, and the sn weight tiles of a column of super-tiles
+// stay in the die's L2 while they fit.  Among the shapes that fit the tile grid, the one that makes
+// a die read the fewest bytes wins (for the V3 shape 2 x 16: a die then owns one 4096-column block
+// of the weights, 3 MiB, and reads the latent once instead of twice).  A small tile grid gets fewer
+// slots, so that there are at least as many super-tiles as dies and every die (and its share of
+// the memory channels) takes part.
+void choose_super(GemmArgs& a, int max_slots, int bt, int bn)
 {
     auto pow2ceil = [](int v) { int p = 1; while (p < v) p *= 2; return p; };
     const int mcap = pow2ceil(a.m_tiles), ncap = pow2ceil(a.n_tiles);
+    const double tok_tile = (double)bt * (a.K + a.a_skip) * 2.0, wgt_tile = (double)bn * a.K * 2.0;
+    const double l2_budget = 3.0 * 1024 * 1024;            // of the die's 4 MiB
     for (int slots = max_slots;; slots /= 2) {
-        int sm = slots >= 64 ? 8 : slots >= 16 ? 4 : slots >= 4 ? 2 : 1;
-        while (sm > 1 && sm > mcap) sm /= 2;                       // no slots for missing token tiles
-        while (slots / sm > ncap && sm * 2 <= mcap) sm *= 2;       // nor for missing column tiles
-        const int sn = slots / sm;
-        const int64_t n_super = (int64_t)((a.m_tiles + sm - 1) / sm) * ((a.n_tiles + sn - 1) / sn);
-        if (n_super >= kNumXcd || slots == 1) {
-            a.sm = sm;
-            a.sn = sn;
+        int best_sm = 0;
+        double best_cost = 0.0;
+        for (int sm = 1; sm <= slots; sm *= 2) {
+            const int sn = slots / sm;
+            if ((sm > mcap && sm > 1) || (sn > ncap && sn > 1)) continue;   // no slots for tiles that do not exist
+            const int64_t nsm = (a.m_tiles + sm - 1) / sm, nsn = (a.n_tiles + sn - 1) / sn;
+            const int64_t total = nsm * nsn;
+            if (total < kNumXcd && slots > 1) continue;
+            const int64_t per_die = (total + kNumXcd - 1) / kNumXcd;
+            const int64_t passes = (per_die + nsm - 1) / nsm;              // columns of super-tiles a die touches
+            const double w_reads = sn * wgt_tile <= l2_budget ? (double)passes * sn : (double)per_die * sn;
+            const double cost = (double)per_die * sm * tok_tile + w_reads * wgt_tile;
+            if (best_sm == 0 || cost < best_cost * 0.999) { best_sm = sm; best_cost = cost; }
+        }
+        if (best_sm || slots == 1) {
+            a.sm = best_sm ? best_sm : 1;
+            a.sn = slots / a.sm;
             return;
         }
     }
@@ -310,13 +327,13 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         const bool stream = big && stream_ok;
         if (big) {
             build_tiles(a, G, group_cols, half_tokens ? 128 : 256, 256);
-            choose_super(a, kSlotsPerXcd);
+            choose_super(a, kSlotsPerXcd, half_tokens ? 128 : 256, 256);
             // identity slice: stages of the streaming kernel (the slice of a 256-column tile is the
             // whole window, or the tile's own 256 columns of it when d_h is a multiple of 256)
             a.n_stage_id = plain ? n_stage_id_lean : n_stage_id;
         } else {
             build_tiles(a, G, group_cols, 128, 128);
-            choose_super(a, 2 * kSlotsPerXcd);
+            choose_super(a, 2 * kSlotsPerXcd, 128, 128);
         }
 #define BDA_LAUNCH(X, O)                                      \
     return stream ? launch_stream<X, O>(a, plain, half_tokens, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)

@@ -258,7 +258,7 @@ def test_launch_plan_benchmark_shapes():
 def test_launch_plan_tile_choice_by_rounds():
     """128-token tiles where they need fewer than 1/0.56 times the rounds of 256-token tiles; dies
     take single tiles where whole super-tiles would need more rounds."""
-    want = {600: (128, 1, 0), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
+    want = {600: (128, 1, 1), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
             3072: (256, 1, 1), 4096: (256, 1, 0), 5120: (128, 3, 0), 8192: (256, 2, 0)}
     for T, (tokens, rounds, by_tile) in want.items():
         p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
