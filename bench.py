@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--rotate", type=int, default=2, help="distinct (c, out) buffer pairs of the main workload")
     ap.add_argument("--workload", choices=("v3", "v2lite"), default="v3")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--tile-policy", type=int, default=0,
+                    help="tile policy of the main workload's launches (0 = the library's own choice; see include/bda.h)")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="leave the token-count sweep out of the extras")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -229,8 +231,8 @@ def main() -> int:
         c_bufs.append(dev(cw.c_stored, w.dtype))
         o_bufs.append(torch.empty((T, N), dtype=tdt[w.dtype], device="cuda"))
 
-    main_fn = lambda i, s: bda.bda_kv_project(c_bufs[i % R], d_c, T, d_c, d_h, H, offs, C_d, N,       # noqa: E731
-                                              o_bufs[i % R], N, w.dtype, w.dtype, s)
+    main_fn = lambda i, s: bda.bda_kv_project_ex(c_bufs[i % R], d_c, T, d_c, d_h, H, offs, C_d, N,    # noqa: E731
+                                                 o_bufs[i % R], N, w.dtype, w.dtype, s, args.tile_policy)
     main_step = Step(main_fn)
     # The chip needs on the order of 100 ms of work to reach its steady clock / power state: a
     # measurement taken after a cold start reads differently from the same launches a moment later
@@ -272,7 +274,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": tag, "T": T, "d_c": d_c, "d_h": d_h, "heads": H,
                    "basis_offset": offs, "N": N, "K": K, "rotating_buffers": R, "weights": "bda_prepare (host fp64), first-r basis",
-                   "launch": "hip_graph" if use_graph else "loop", "prewarm_ms": args.prewarm_ms},
+                   "launch": "hip_graph" if use_graph else "loop", "prewarm_ms": args.prewarm_ms,
+                   "tile_policy": args.tile_policy},
         "roofline": {"bound": "mfma", "achieved": flops / kernel_s / 1e12, "peak": MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops / kernel_s / 1e12 / MFMA_PEAK_TFLOPS,
                      "traffic": traffic,

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     BdaError, load, lib_path, exported_symbols,
     bda_prepare, bda_prepare_lowrank, bda_prepare_device, bda_kv_project, bda_dense_project, bda_lowrank_linear,
     bda_kv_project_backward, bda_kv_project_plan, bda_dense_project_plan, LaunchPlan,
-    KERNEL_NONE, KERNEL_GENERAL, KERNEL_MFMA, KERNEL_STREAM, KERNEL_LEAN, KERNEL_DECODE,
+    KERNEL_NONE, KERNEL_GENERAL, KERNEL_MFMA, KERNEL_STREAM, KERNEL_LEAN, KERNEL_DECODE, KERNEL_DUO,
     bda_kv_project_ex, bda_dense_project_ex, bda_kv_project_backward_ex, bda_last_error, bda_version,
 )

@@ -26,7 +26,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _lib = None
 
 
-KERNEL_NONE, KERNEL_GENERAL, KERNEL_MFMA, KERNEL_STREAM, KERNEL_LEAN, KERNEL_DECODE = 0, 1, 2, 3, 4, 5
+KERNEL_NONE, KERNEL_GENERAL, KERNEL_MFMA, KERNEL_STREAM, KERNEL_LEAN, KERNEL_DECODE, KERNEL_DUO = 0, 1, 2, 3, 4, 5, 6
 
 
 class LaunchPlan(ctypes.Structure):

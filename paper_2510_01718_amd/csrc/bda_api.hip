@@ -8,6 +8,7 @@
 #include "bda_decode.hpp"
 #include "bda_gemm_stream.hpp"
 #include "bda_gemm_plain.hpp"
+#include "bda_gemm_duo.hpp"
 #include "bda_internal.h"
 
 namespace bda {
@@ -116,6 +117,69 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
     if (half_tokens) hipLaunchKernelGGL(kern_half, dim3(kNumXcd * wgs_per_die), dim3(512), lds_half, st, a);
     else if (plain) hipLaunchKernelGGL(kern_plain, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
     else hipLaunchKernelGGL(kern, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
+}
+
+// Two-workgroups-per-compute-unit kernel (bda_gemm_duo.hpp); a's tile grid is 128 x 256.  The eight
+// dies split the grid into dn column ranges x dm token ranges (dn dm = 8): the split with the fewest
+// rounds of tiles wins, then the one whose dies read the fewest bytes.
+template <typename X, typename OutT>
+int launch_duo(const GemmArgs& a, hipStream_t st)
+{
+    static LdsLimitState once_id, once_plain;
+    DuoArgs d{};
+    d.A = a.A; d.B = a.B; d.D = a.D;
+    d.lda = a.lda; d.ldb = a.ldb; d.ldd = a.ldd;
+    d.M = a.M; d.K = a.K; d.n_groups = a.n_groups; d.d_h = a.d_h; d.a_skip = a.a_skip;
+    for (int g = 0; g <= kMaxGroups; ++g) { d.tile_start[g] = a.tile_start[g]; d.col_start[g] = a.col_start[g]; }
+    for (int g = 0; g < kMaxGroups; ++g) d.a_off[g] = a.a_off[g];
+    const double tok_tile = 128.0 * (a.K + a.a_skip) * 2.0, wgt_tile = 256.0 * a.K * 2.0;
+    const double l2_budget = 3.0 * 1024 * 1024;            // of the die's 4 MiB
+    int best_dn = 0;
+    int64_t best_rounds = 0;
+    double best_cost = 0.0;
+    for (int dn = kNumXcd; dn >= 1; dn /= 2) {
+        const int dm = kNumXcd / dn;
+        const int64_t cx = (a.n_tiles + dn - 1) / dn, mx = (a.m_tiles + dm - 1) / dm;
+        const int64_t rounds = (cx * mx + kDuoSlotsPerXcd - 1) / kDuoSlotsPerXcd;
+        // a die streams its token tiles once; its column range of the weights once if that stays in
+        // its L2, else once per round
+        const double w_reads = cx * wgt_tile <= l2_budget ? (double)cx : (double)rounds * std::min<int64_t>(cx, kDuoSlotsPerXcd);
+        const double cost = mx * tok_tile + w_reads * wgt_tile;
+        if (!best_dn || rounds < best_rounds || (rounds == best_rounds && cost < best_cost * 0.999)) {
+            best_dn = dn; best_rounds = rounds; best_cost = cost;
+        }
+    }
+    const int dn = best_dn, dm = kNumXcd / dn;
+    for (int x = 0; x < kNumXcd; ++x) {
+        const int xn = x % dn, xm = x / dn;
+        // nearly equal ranges: the first (tiles % parts) ranges are one longer
+        auto range = [](int tiles, int parts, int i, int& first, int& count) {
+            const int base = tiles / parts, extra = tiles % parts;
+            first = i * base + std::min(i, extra);
+            count = base + (i < extra ? 1 : 0);
+        };
+        range(a.n_tiles, dn, xn, d.die_c0[x], d.die_cx[x]);
+        range(a.m_tiles, dm, xm, d.die_m0[x], d.die_mx[x]);
+        const int cx = std::max(d.die_cx[x], 1);
+        d.die_magic[x] = (((uint64_t)1 << 40) + cx - 1) / cx;
+    }
+    d.rounds = (int)best_rounds;
+    if (t_plan) {
+        *t_plan = bda_launch_plan{BDA_KERNEL_DUO, 128, 256, a.m_tiles, a.n_tiles, kNumXcd * kDuoSlotsPerXcd, kDuoThreads,
+                                  kDuoLdsBytes, d.rounds, 1, dm, dn};
+        return BDA_OK;
+    }
+    if (a.ident) {
+        auto kern = gemm_duo_kernel<X, OutT, true>;
+        if (int rc = set_max_lds(kern, kDuoLdsBytes, once_id)) return rc;
+        hipLaunchKernelGGL(kern, dim3(kNumXcd * kDuoSlotsPerXcd), dim3(kDuoThreads), kDuoLdsBytes, st, d);
+    } else {
+        auto kern = gemm_duo_kernel<X, OutT, false>;
+        if (int rc = set_max_lds(kern, kDuoLdsBytes, once_plain)) return rc;
+        hipLaunchKernelGGL(kern, dim3(kNumXcd * kDuoSlotsPerXcd), dim3(kDuoThreads), kDuoLdsBytes, st, d);
+    }
     hipError_t err = hipGetLastError();
     return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "kernel launch: %s", hipGetErrorString(err));
 }
@@ -267,7 +331,16 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     // blocks while every slice has a compute unit of its own (N = 4096: 5.8-7.3 against 10.6 with
     // 128-token tiles), then 64-column slices while those have (N = 12288 .. 16384: 8.4-9.4 against
     // 10.7-11.0), the tiles beyond (N = 24576: 11.3 against 15-16).
-    const int policy0 = t_policy;
+    // Can the two-workgroups-per-compute-unit kernel take this launch (the lean kernel's preconditions
+    // with stages of 32 and identity slices of 64- or 128-wide heads)?  Policy 6 asks for it wherever
+    // it can and otherwise acts as 0.
+    bool duo_ok = fast && a.K % 32 == 0 && a.K >= 64 && (!a.ident || a.d_h == 64 || a.d_h == 128);
+    {
+        int64_t nt256 = 0;
+        for (int g = 0; g < G; ++g) { duo_ok = duo_ok && group_cols[g] % 256 == 0; nt256 += (group_cols[g] + 255) / 256; }
+        duo_ok = duo_ok && ((a.M + 127) / 128) * nt256 < ((int64_t)1 << 24);
+    }
+    const int policy0 = (t_policy == 6 && !duo_ok) ? 0 : t_policy;
     const bool small_policy = policy0 == 0 || policy0 == 5;
     int64_t n_slices128 = 0, n_slices64 = 0, n_slices32 = 0;
     for (int g = 0; g < G; ++g) {
@@ -322,6 +395,14 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
             const int64_t run = (tiles + kNumXcd - 1) / kNumXcd;
             return (run + kSlotsPerXcd - 1) / kSlotsPerXcd;
         };
+        if (policy == 6) {
+            build_tiles(a, G, group_cols, 128, 256);
+            a.sm = a.sn = 1;
+            if (dtype == BDA_F16 && out_dtype == BDA_F16) return launch_duo<F16, uint16_t>(a, st);
+            if (dtype == BDA_F16 && out_dtype == BDA_F32) return launch_duo<F16, float>(a, st);
+            if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_duo<BF16, uint16_t>(a, st);
+            if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_duo<BF16, float>(a, st);
+        }
         const bool half_tokens = plain && (policy == 4 || (policy == 0 && 0.56 * (double)rounds_of(mt128 * nt256) < (double)rounds_of(mt256 * nt256)));
         const bool big = plain || policy == 2 || policy == 3 || policy == 4 || (policy == 0 && mt256 * nt256 >= 96);
         const bool stream = big && stream_ok;
@@ -371,7 +452,7 @@ PolicyScope::~PolicyScope() { t_policy = prev_; }
 
 int check_policy(const char* fn, int policy)
 {
-    return policy >= 0 && policy <= 5 ? BDA_OK : fail(BDA_EINVAL, "%s: tile_policy must be 0 .. 5 (got %d)", fn, policy);
+    return policy >= 0 && policy <= 6 ? BDA_OK : fail(BDA_EINVAL, "%s: tile_policy must be 0 .. 6 (got %d)", fn, policy);
 }
 
 }  // namespace bda

@@ -186,11 +186,11 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert bwd(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None) == 0
     assert lib.bda_dense_project(fake, 64, 4, 64, fake, 8, 32, fake, 32, 1, 1, None) == -1
     assert lib.bda_lowrank_linear(fake, 64, 4, 64, 8, 40, 3, fake, fake, fake, 40, 1, None) == -1
-    # a tile policy outside 0 .. 5 is refused before anything else is looked at
+    # a tile policy outside 0 .. 6 is refused before anything else is looked at
     assert lib.bda_kv_project_ex(fake, 64, 4, 64, 16, 1, H, off, fake, 32, far, 32, 1, 1, None, 7) == -1
     assert b"tile_policy" in lib.bda_last_error()
     assert lib.bda_dense_project_ex(fake, 64, 4, 64, fake, 32, 32, far, 32, 1, 1, None, -1) == -1
-    assert lib.bda_kv_project_backward_ex(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None, 6) == -1
+    assert lib.bda_kv_project_backward_ex(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None, 7) == -1
 
 
 def test_workload_recipe_is_stable():
@@ -291,6 +291,10 @@ def test_launch_plan_preconditions_of_the_lean_kernel():
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=1)["kernel"] == bda.KERNEL_MFMA
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=3)["kernel"] == bda.KERNEL_STREAM
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=4)["tile_tokens"] == 128
+    duo = _plan(8192, [128, 128], [0, 0], bda.BDA_BF16, tile_policy=6)       # two 4-wave workgroups per compute unit
+    assert (duo["kernel"], duo["tile_tokens"], duo["workgroups"], duo["threads"], duo["rounds"]) == (bda.KERNEL_DUO, 128, 512, 256, 16)
+    assert (duo["super_m"], duo["super_n"]) == (1, 8)                          # eight column ranges: one die keeps 16 column tiles of weights
+    assert _plan(300, [4], [64], bda.BDA_F16, d_c=448, d_h=192, tile_policy=6) == _plan(300, [4], [64], bda.BDA_F16, d_c=448, d_h=192)
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16)["kernel"] == lean          # and nothing of it outlives the call
     with pytest.raises(bda.BdaError):
         _plan(4096, [16, 16], [0, 400], bda.BDA_F16)                    # window outside the latent
