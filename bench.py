@@ -305,6 +305,7 @@ def main() -> int:
             yl.bdy_read.argtypes = [vp, u64, vp, ci, vp]
             yl.bdy_write.argtypes = [vp, u64, u32, ci, ci, vp]
             yl.bdy_copy.argtypes = [vp, vp, u64, ci, vp]
+            yl.bdy_stage_model.argtypes = [vp, u64, ci, ci, vp, vp]
             sink = torch.zeros(64, dtype=torch.int32, device="cuda")
             y = {}
 
@@ -318,6 +319,19 @@ def main() -> int:
                 for rnd, sfx in ((0, ""), (1, "_random_data")):
                     t_m = bench_fixed(lambda i, s: ck(yl.bdy_mfma_loop(512, it, bf, rnd, sink.data_ptr(), s or None)))
                     y[f"mfma_loop_{nm}{sfx}_tflops"] = 512 * 4 * it * 4 * 32768.0 / t_m / 1e12
+            # The stage model: MFMAs + LDS fragment reads (+ DMA loads, load wait and barrier) of a 256 x 256 x 64
+            # stage at the large-T kernels' ratios, nothing else; bf16 operands 0.5 <= |v| < 2 with random
+            # signs and mantissas (what a launch on real data feeds the matrix cores), then zeros.
+            win = 2 << 20
+            g = torch.Generator(device="cuda").manual_seed(7)
+            bits = torch.randint(0, 1 << 16, (8 * win // 2,), dtype=torch.int32, device="cuda", generator=g)
+            model_src = ((bits & 0x80FF) | 0x3F00).to(torch.int16)       # sign, exponent 126 / 127, seven mantissa bits
+            n_st = 1000
+            for sfx, buf in (("random_data", model_src), ("zeros", torch.zeros_like(model_src))):
+                for full, nm in ((0, "mfma_lds"), (1, "full")):
+                    t_s = bench_fixed(lambda i, s: ck(yl.bdy_stage_model(buf.data_ptr(), win, n_st, full, sink.data_ptr(), s or None)))
+                    y[f"stage_model_{nm}_{sfx}_tflops"] = 256 * 8 * 32 * 32768.0 * n_st / t_s / 1e12
+            del bits, model_src
             big = 2 << 30                                      # 2 GiB: eight times the last-level cache
             src = torch.empty(big, dtype=torch.uint8, device="cuda").fill_(3)
             dst = torch.empty(big, dtype=torch.uint8, device="cuda")
@@ -333,6 +347,7 @@ def main() -> int:
             result["roofline"]["frac_of_measured_mfma_loop"] = result["roofline"]["achieved"] / y[f"mfma_loop_{wl.DTYPE_NAMES[w.dtype]}_tflops"]
             result["roofline"]["frac_of_measured_mfma_loop_random_data"] = (
                 result["roofline"]["achieved"] / y[f"mfma_loop_{wl.DTYPE_NAMES[w.dtype]}_random_data_tflops"])
+            result["roofline"]["frac_of_stage_model_random_data"] = result["roofline"]["achieved"] / y["stage_model_full_random_data_tflops"]
 
         # ---- dense comparator of the main workload, timed alternately with the BD launch
         W_stored, _ = wl.to_storage(w.W, w.dtype)
