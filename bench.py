@@ -509,6 +509,40 @@ def main() -> int:
             t_p = bench_fixed(lambda i, s: bda.bda_prepare_device(Wp, Hh * d_h, wl.F32, d_c, Hh, d_h, 0, Cp, Hh * d_h, cdt, flag, s), graph=False)
             prep[f"device_{nm}_us"] = t_p * 1e6
             assert int(flag.item()) == 0
+        # One layer of the V2-Lite shape prepared on the GPU as the paper's algorithms do it: keys with the query
+        # weight as companion (16 heads, W_q 2048 x 2048), values with the output weight (W_o 2048 x 2048), C and the
+        # companion stored in fp16, window by Residual-min and by offset search (25 candidate windows).  A model has
+        # 27 such layers (context: the paper's preparation-time table is for whole models on other hardware).
+        Hl, d_model = 16, 2048
+        Wl = torch.randn((d_c, Hl * d_h), dtype=torch.float32, device="cuda") * 0.02
+        Wq_l = torch.randn((d_model, Hl * d_h), dtype=torch.float32, device="cuda") * 0.02
+        Wo_l = torch.randn((Hl * d_h, d_model), dtype=torch.float32, device="cuda") * 0.02
+        Cl = torch.empty((K, Hl * d_h), dtype=torch.float16, device="cuda")
+        Sq = torch.empty_like(Wq_l, dtype=torch.float16)
+        So = torch.empty_like(Wo_l, dtype=torch.float16)
+        off_l = torch.zeros(1, dtype=torch.int32, device="cuda")
+        res_l = torch.zeros(3, dtype=torch.float64, device="cuda")
+        for mode, mname in ((bda.BASIS_RESIDUAL_MIN, "residual_min"), (bda.BASIS_OFFSET_SEARCH, "offset_search")):
+            nb = bda.bda_prepare_device_workspace_bytes(d_c, Hl, d_h, mode, True)
+            ws_l = torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+            def layer(i, s):
+                flag.zero_()
+                bda.bda_prepare_device_ex(Wl, Hl * d_h, wl.F32, d_c, Hl, d_h, Cl, Hl * d_h, wl.F16, side=Wq_l, ld_side=Hl * d_h,
+                                          d_side=d_model, side_kind=bda.SIDE_Q, side_out=Sq, ld_side_out=Hl * d_h, mode=mode,
+                                          basis_offset_out=off_l, resid_out=res_l, singular_head=flag, workspace=ws_l,
+                                          workspace_bytes=nb, stream=s)
+                bda.bda_prepare_device_ex(Wl, Hl * d_h, wl.F32, d_c, Hl, d_h, Cl, Hl * d_h, wl.F16, side=Wo_l, ld_side=d_model,
+                                          d_side=d_model, side_kind=bda.SIDE_O, side_out=So, ld_side_out=d_model, mode=mode,
+                                          basis_offset_out=off_l, resid_out=res_l, singular_head=flag, workspace=ws_l,
+                                          workspace_bytes=nb, stream=s)
+            layer(0, sid)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            layer(0, sid)
+            torch.cuda.synchronize()
+            prep[f"device_v2lite_layer_k_and_v_with_companions_{mname}_ms"] = (time.perf_counter() - t0) * 1e3
+            assert int(flag.item()) == 0 and int(off_l.item()) >= 0
         extra["prepare"] = prep
         log("prepare: " + ", ".join(f"{k} {v:.3g}" for k, v in prep.items()))
     result["extra"] = extra

@@ -100,21 +100,58 @@ int bda_prepare_lowrank(const double* U, const double* V, int d_in, int r, int d
                         double* resid_out);
 
 /*
- * The same C as bda_prepare, computed on the GPU for an explicit basis window (Algorithm "BD Attention
- * Preparation (QK)" and Appendix "BD for VO in MHA": C_h = W_h[Bbar,:] W_h[B,:]^{-1}, one workgroup per
- * head, float64 arithmetic: Gauss-Jordan inverse of the basis block with partial pivoting, then the
- * product).  The window is chosen by the caller (0 = first, d_c - d_h = last, or the offset that
- * bda_prepare's residual search returned); companion weights are not handled here.
+ * bda_prepare on the GPU (Algorithm "BD Attention Preparation (QK)", Appendix "BD for VO in MHA",
+ * Algorithm "BD Decomposition (Row)" and Appendix "Residual-Min with Offset Search" for the window
+ * choice): C_h = W_h[Bbar,:] W_h[B,:]^{-1}, the companion blocks W_q^h W_h[B,:]^T or W_h[B,:] W_o^h,
+ * and the window that minimises the mean residual of the stored form.  One workgroup per head,
+ * float64 arithmetic (Gauss-Jordan inverse of the basis block with partial pivoting, then the
+ * products); a search prepares every candidate window in turn into the outputs, measures the
+ * reconstruction error of what was stored, selects on the device, and prepares the chosen window once
+ * more.  Asynchronous on `stream`; nothing comes back to the host and nothing is allocated.
  *   W        device, d_c x (H d_h), ld = ldw, element type w_dtype (any bda_dtype).
+ *   side     device or NULL: companion weight as in bda_prepare (W_q: d_side x H d_h; W_o: H d_h x
+ *            d_side), ld = ld_side, element type w_dtype.
+ *   mode, explicit_offset   as in bda_prepare (candidate windows, ranking, ties, NaN); a window with a
+ *            numerically singular basis block in any head (pivot below d_h * 2^-52 * ||W_h[B,:]||_F)
+ *            ranks last and is never chosen by a search.
  *   C        device, (d_c - d_h) x (H d_h), ld = ldC, element type c_dtype (any bda_dtype); every
  *            element is rounded once, to nearest even, from the float64 result - ready for
  *            bda_kv_project.
+ *   side_out device (NULL without a companion), shape of `side`, ld = ld_side_out, element type
+ *            c_dtype, rounded the same way.
+ *   basis_offset_out   device int (may be NULL for a single-window mode without resid_out): the
+ *            chosen window start once the call has run, or -1 if every candidate was singular (C
+ *            and side_out then hold no result).
+ *   resid_out   device, NULL or 3 doubles: mean residual of the first, the last and the chosen window
+ *            (NaN where a window was not a candidate, +inf for a singular one).
  *   singular_head   device int or NULL; the caller zeroes it; after the call has run it holds
- *            1 + the largest index of a head whose basis block was numerically singular (pivot
- *            below d_h * 2^-52 * ||W_h[B,:]||_F), or stays 0.  C of such a head is not written.
- * Asynchronous on `stream`; allocates nothing.  d_h <= 128.  Agrees with bda_prepare to a small
- * multiple of cond(W_h[B,:]) * 2^-53 (a different elimination order), not bit for bit.
- * Errors: BDA_EINVAL, BDA_EDTYPE, BDA_EHIP.
+ *            1 + the largest index of a head whose basis block was singular in the window that was
+ *            finally prepared, or stays 0.  C of such a head is not written.
+ *   workspace, workspace_bytes   device memory for the call's partial results, 16-byte aligned: one
+ *            flag per candidate window, the per-head partial sums of the residuals, and - for d_h >
+ *            128, whose basis block does not fit the LDS - one d_h x d_h float64 block per head
+ *            prepared at a time.  bda_prepare_device_workspace_bytes() gives a sufficient size
+ *            (0: none needed, which is the case for a single-window mode without resid_out and d_h
+ *            <= 128; workspace may then be NULL); any size from one block upwards works for d_h >
+ *            128, more blocks meaning more heads per launch.  Contents before and after are
+ *            meaningless; calls that share a workspace must not overlap.
+ * d_h <= 256, at most 256 candidate windows.  Agrees with bda_prepare to a small multiple of
+ * cond(W_h[B,:]) * 2^-53 (a different elimination order), not bit for bit; the chosen window agrees
+ * unless two candidates' residuals are that close.
+ * Errors: BDA_EINVAL (also: workspace too small, message says how much is needed), BDA_EDTYPE,
+ * BDA_EHIP.
+ */
+size_t bda_prepare_device_workspace_bytes(int d_c, int H, int d_h, bda_basis_mode mode, int want_residuals);
+int bda_prepare_device_ex(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
+                          const void* side, int64_t ld_side, int d_side, bda_side side_kind,
+                          bda_basis_mode mode, int explicit_offset,
+                          void* C, int64_t ldC, void* side_out, int64_t ld_side_out, bda_dtype c_dtype,
+                          int* basis_offset_out, double* resid_out, int* singular_head,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The short form: C only, for an explicit window (0 = first, d_c - d_h = last, or the offset a search
+ * returned), d_h <= 128, no workspace.  Arguments as above.
  */
 int bda_prepare_device(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
                        int basis_offset, void* C, int64_t ldC, bda_dtype c_dtype,

@@ -18,7 +18,8 @@ BDA_F32, BDA_F16, BDA_BF16, BDA_F64 = 0, 1, 2, 3
 BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT = 0, 1, 2, 3, 4
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
-EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_kv_project", "bda_dense_project",
+EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_prepare_device_ex",
+           "bda_prepare_device_workspace_bytes", "bda_kv_project", "bda_dense_project",
            "bda_lowrank_linear", "bda_kv_project_backward", "bda_kv_project_ex", "bda_dense_project_ex",
            "bda_kv_project_backward_ex", "bda_kv_project_plan", "bda_dense_project_plan", "bda_last_error", "bda_version")
 
@@ -70,6 +71,11 @@ def load():
     lib.bda_prepare_lowrank.argtypes = [dp, dp, c_int, c_int, c_int, c_int, c_int, dp, dp, ip, dp]
     lib.bda_prepare_device.restype = c_int
     lib.bda_prepare_device.argtypes = [vp, i64, c_int, c_int, c_int, c_int, c_int, vp, i64, c_int, vp, vp]
+    lib.bda_prepare_device_workspace_bytes.restype = ctypes.c_size_t
+    lib.bda_prepare_device_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int]
+    lib.bda_prepare_device_ex.restype = c_int
+    lib.bda_prepare_device_ex.argtypes = [vp, i64, c_int, c_int, c_int, c_int, vp, i64, c_int, c_int, c_int, c_int,
+                                          vp, i64, vp, i64, c_int, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.bda_kv_project.restype = c_int
     lib.bda_kv_project.argtypes = [vp, i64, i64, c_int, c_int, c_int, ip, ip, vp, i64, vp, i64,
                                    c_int, c_int, vp]
@@ -209,6 +215,23 @@ def bda_prepare_device(W, ldw: int, w_dtype: int, d_c: int, H: int, d_h: int, ba
     lib = load()
     _check(lib.bda_prepare_device(_ptr(W), ldw, w_dtype, d_c, H, d_h, basis_offset, _ptr(C), ldC, c_dtype,
                                   _ptr(singular_head), stream or None))
+
+
+def bda_prepare_device_workspace_bytes(d_c: int, H: int, d_h: int, mode: int, want_residuals: bool = False) -> int:
+    return int(load().bda_prepare_device_workspace_bytes(d_c, H, d_h, mode, 1 if want_residuals else 0))
+
+
+def bda_prepare_device_ex(W, ldw: int, w_dtype: int, d_c: int, H: int, d_h: int, C, ldC: int, c_dtype: int,
+                          side=None, ld_side: int = 0, d_side: int = 0, side_kind: int = SIDE_NONE,
+                          side_out=None, ld_side_out: int = 0, mode: int = BASIS_FIRST, explicit_offset: int = 0,
+                          basis_offset_out=None, resid_out=None, singular_head=None,
+                          workspace=None, workspace_bytes: int = 0, stream: int = 0) -> None:
+    """All array arguments are device arrays (anything with data_ptr()); see include/bda.h."""
+    lib = load()
+    _check(lib.bda_prepare_device_ex(_ptr(W), ldw, w_dtype, d_c, H, d_h, _ptr(side), ld_side, d_side, side_kind,
+                                     mode, explicit_offset, _ptr(C), ldC, _ptr(side_out), ld_side_out, c_dtype,
+                                     _ptr(basis_offset_out), _ptr(resid_out), _ptr(singular_head),
+                                     _ptr(workspace), int(workspace_bytes), stream or None))
 
 
 def bda_dense_project(c, ldc: int, T: int, d_c: int, W, ldW: int, N: int, out, ld_out: int,

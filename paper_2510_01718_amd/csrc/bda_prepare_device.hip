@@ -1,10 +1,21 @@
-// GPU preparation of the BD projection weights:  C_h = W_h[Bbar,:] W_h[B,:]^{-1}  for an explicit basis
-// window (Algorithm "BD Attention Preparation (QK)" / Appendix "BD for VO in MHA", the part that does
-// not depend on the companion weight).  One workgroup per head, float64 throughout:
-//   1. the d_h x d_h basis block is copied into LDS and inverted in place by Gauss-Jordan elimination
-//      with partial (row) pivoting; the row interchanges are undone as column interchanges at the end;
-//   2. the (d_c - d_h) rows outside the window are multiplied by the inverse, 16 rows at a time staged
-//      through LDS, and stored rounded to the requested type.
+// GPU preparation of one projection (Algorithm "BD Attention Preparation (QK)", Appendix "BD for VO in
+// MHA", Algorithm "BD Decomposition (Row)" for the window choice, Appendix "Residual-Min with Offset
+// Search" for the candidate windows).  Float64 throughout, four kernels:
+//   prepare_kernel   C_h = W_h[Bbar,:] W_h[B,:]^{-1}, one workgroup per head: the d_h x d_h basis block
+//                    is inverted in place by Gauss-Jordan elimination with partial (row) pivoting (in
+//                    LDS up to d_h = 128, in the caller's workspace up to 256; the row interchanges are
+//                    undone as column interchanges at the end), then the d_c - d_h rows outside the
+//                    window are multiplied by the inverse, 16 rows at a time staged through LDS, and
+//                    stored rounded to the requested type;
+//   side_kernel      the companion block: W_q^h W_h[B,:]^T or W_h[B,:] W_o^h, rounded the same way;
+//   residual_kernel  the Frobenius reconstruction error of the stored form of one head - what was just
+//                    written to C and to the companion output, read back - as partial sums of squares
+//                    (a fixed number of parts per head, each summed in a fixed order);
+//   select_kernel    per candidate window the mean over heads of the residuals, the smallest mean
+//                    (earlier candidate on ties, NaN as +inf), the chosen window start.
+// A search runs prepare / side / residual once per candidate window into the caller's outputs, selects,
+// and runs prepare / side once more for the chosen window, whose start it reads from device memory:
+// nothing comes back to the host in between.
 // The host routine bda_prepare solves with an orthogonal factorisation instead of forming the inverse;
 // the two agree to a small multiple of cond(W_h[B,:]) * 2^-53.
 #include <hip/hip_runtime.h>
@@ -15,14 +26,6 @@
 
 namespace bda {
 namespace {
-
-struct PrepArgs {
-    const void* W;
-    void* C;
-    int* status;
-    int64_t ldw, ldC;
-    int d_c, H, d_h, off;
-};
 
 template <typename T> __device__ __forceinline__ double load_as_double(const void* p, int64_t i);
 template <> __device__ __forceinline__ double load_as_double<double>(const void* p, int64_t i) { return ((const double*)p)[i]; }
@@ -61,31 +64,62 @@ template <> __device__ __forceinline__ void store_rounded<__bf16>(void* p, int64
 }
 
 constexpr int kPrepThreads = 256;
-constexpr int kPrepMaxDh = 128;
+constexpr int kPrepLdsDh = 128;               // largest head width whose basis block is inverted in LDS
+constexpr int kPrepMaxDh = 256;               // largest head width at all (block in the workspace)
 constexpr int kPrepRows = 16;                 // rows of W_h[Bbar,:] staged per pass
+constexpr int kMaxCandidates = 256;
+constexpr int kMaxParts = 16;
 
-template <typename WT, typename CT>
+struct PrepArgs {
+    const void* W;
+    const void* side;            // companion weight (type of W) or NULL
+    void* C;
+    void* side_out;              // companion output (type of C) or NULL
+    int* status;                 // singular_head of the public calls, or NULL
+    const int* off_ptr;          // device: window start chosen by select_kernel (NULL: `off`)
+    int* cand_singular;          // workspace: one flag per candidate window, or NULL
+    double* partials;            // workspace: [candidate][head][part] sums of squares, or NULL
+    double* mat;                 // workspace: one d_h x d_h block per workgroup of a batch (d_h > 128), or NULL
+    int64_t ldw, ld_side, ldC, ld_side_out;
+    int d_c, H, d_h, off, d_side, side_kind;
+    int h0;                      // first head of this launch (batches when the block lives in the workspace)
+    int cand, n_parts;
+};
+
+__device__ __forceinline__ int window_start(const PrepArgs& a) { return a.off_ptr ? *a.off_ptr : a.off; }
+
+// BIG: the basis block lives in global memory (a.mat, one block per workgroup) instead of LDS.
+template <typename WT, typename CT, bool BIG>
 __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     const int n = a.d_h;
-    const int ld = n + 1;                      // odd stride in doubles: a column walk touches all banks
-    double* A = (double*)smem_raw;             // n x ld: the basis block, then its inverse
-    double* R = A + (size_t)n * ld;            // kPrepRows x n staging, also scratch for the pivot search
+    const int ld = BIG ? n : n + 1;            // LDS: odd stride in doubles, a column walk touches all banks
+    double* R;                                 // kPrepRows x n staging, also scratch for the reductions
+    double* A;                                 // n x ld: the basis block, then its inverse
+    if constexpr (BIG) {
+        R = (double*)smem_raw;
+        A = a.mat + (size_t)blockIdx.x * n * n;
+    } else {
+        A = (double*)smem_raw;
+        R = A + (size_t)n * ld;
+    }
     __shared__ int piv[kPrepMaxDh];
     __shared__ int s_pivot_row;
     __shared__ double s_pivot_val;
     __shared__ int s_singular;
 
     const int t = threadIdx.x;
-    const int h = blockIdx.x;
+    const int h = a.h0 + blockIdx.x;
+    const int off = window_start(a);
+    if (off < 0) return;                       // no usable window was found: nothing to prepare
     const int64_t col0 = (int64_t)h * n;
 
     // ---- basis block and its scale --------------------------------------------------------------
     double part = 0.0;
     for (int e = t; e < n * n; e += kPrepThreads) {
         const int i = e / n, j = e % n;
-        const double v = load_as_double<WT>(a.W, (int64_t)(a.off + i) * a.ldw + col0 + j);
+        const double v = load_as_double<WT>(a.W, (int64_t)(off + i) * a.ldw + col0 + j);
         A[i * ld + j] = v;
         part += v * v;
     }
@@ -102,9 +136,11 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
     __syncthreads();
 
     // ---- Gauss-Jordan inversion in place, partial pivoting ----------------------------------------
-    const int row = t % kPrepMaxDh, half = t / kPrepMaxDh;       // thread -> (row, half of the columns)
-    const int jn = (n + 1) / 2;
-    const int j_lo = half * jn, j_hi = (half == 0) ? jn : n;
+    // thread -> (row, segment of the columns): two threads per row up to 128 rows, one per row beyond
+    const int rows_per_pass = n <= 128 ? 128 : 256;
+    const int row = t % rows_per_pass, seg = t / rows_per_pass, n_seg = kPrepThreads / rows_per_pass;
+    const int jn = (n + n_seg - 1) / n_seg;
+    const int j_lo = seg * jn, j_hi = (j_lo + jn < n) ? j_lo + jn : n;
     for (int k = 0; k < n; ++k) {
         // pivot: the largest |A[i][k]|, i >= k (first such row on ties)
         if (t < 64) {
@@ -152,7 +188,10 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
         __syncthreads();
     }
     if (s_singular) {
-        if (t == 0 && a.status) atomicMax(a.status, h + 1);
+        if (t == 0) {
+            if (a.status) atomicMax(a.status, h + 1);
+            if (a.cand_singular) a.cand_singular[a.cand] = 1;    // (every writer stores the same value)
+        }
         return;
     }
     // the elimination inverted P A; A^{-1} = (P A)^{-1} P: undo the interchanges on the columns, last first
@@ -171,57 +210,385 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
 
     // ---- C_h = W_h[Bbar,:] A^{-1} ------------------------------------------------------------------
     const int K = a.d_c - n;
-    const int j = t % kPrepMaxDh, rg = t / kPrepMaxDh;            // output column, row parity
     for (int r0 = 0; r0 < K; r0 += kPrepRows) {
         for (int e = t; e < kPrepRows * n; e += kPrepThreads) {
             const int i = e / n, c = e % n;
             const int r = r0 + i;
-            const int src = r < a.off ? r : r + n;                 // rows outside the window, ascending
+            const int src = r < off ? r : r + n;                   // rows outside the window, ascending
             R[i * n + c] = r < K ? load_as_double<WT>(a.W, (int64_t)src * a.ldw + col0 + c) : 0.0;
         }
         __syncthreads();
+        // thread -> (output column, subset of the staged rows): rows rg, rg + n_rg, ...
+        const int cols_per_pass = n <= 128 ? 128 : 256;
+        const int j = t % cols_per_pass, rg = t / cols_per_pass, n_rg = kPrepThreads / cols_per_pass;
         if (j < n) {
-            double acc[kPrepRows / 2];
+            double acc[kPrepRows];
 #pragma unroll
-            for (int m = 0; m < kPrepRows / 2; ++m) acc[m] = 0.0;
-            for (int k = 0; k < n; ++k) {
-                const double b = A[k * ld + j];
+            for (int m = 0; m < kPrepRows; ++m) acc[m] = 0.0;
+            if (n_rg == 2) {
+                for (int k = 0; k < n; ++k) {
+                    const double b = A[k * ld + j];
 #pragma unroll
-                for (int m = 0; m < kPrepRows / 2; ++m) acc[m] = fma(R[(2 * m + rg) * n + k], b, acc[m]);
-            }
+                    for (int m = 0; m < kPrepRows / 2; ++m) acc[m] = fma(R[(2 * m + rg) * n + k], b, acc[m]);
+                }
 #pragma unroll
-            for (int m = 0; m < kPrepRows / 2; ++m) {
-                const int r = r0 + 2 * m + rg;
-                if (r < K) store_rounded<CT>(a.C, (int64_t)r * a.ldC + col0 + j, acc[m]);
+                for (int m = 0; m < kPrepRows / 2; ++m) {
+                    const int r = r0 + 2 * m + rg;
+                    if (r < K) store_rounded<CT>(a.C, (int64_t)r * a.ldC + col0 + j, acc[m]);
+                }
+            } else {
+                for (int k = 0; k < n; ++k) {
+                    const double b = A[k * ld + j];
+#pragma unroll
+                    for (int m = 0; m < kPrepRows; ++m) acc[m] = fma(R[m * n + k], b, acc[m]);
+                }
+#pragma unroll
+                for (int m = 0; m < kPrepRows; ++m) {
+                    const int r = r0 + m;
+                    if (r < K) store_rounded<CT>(a.C, (int64_t)r * a.ldC + col0 + j, acc[m]);
+                }
             }
         }
         __syncthreads();
     }
 }
 
+// Companion block of head blockIdx.x, rows (Q: rows of W_q; O: window rows) blockIdx.y, + gridDim.y, ...
+//   Q:  side_out[s][h n + i] = sum_j W_q[s][h n + j] W[off + i][h n + j]        (B_qk^h = W_q^h W_h[B,:]^T)
+//   O:  side_out[h n + i][m] = sum_j W[off + i][h n + j] W_o[h n + j][m]        (B_vo^h = W_h[B,:] W_o^h)
 template <typename WT, typename CT>
-int launch_prepare(const PrepArgs& a, hipStream_t st)
+__global__ __launch_bounds__(kPrepThreads) void side_kernel(const PrepArgs a)
+{
+    const int n = a.d_h, h = blockIdx.x, t = threadIdx.x;
+    const int off = window_start(a);
+    if (off < 0) return;
+    const int64_t col0 = (int64_t)h * n;
+    if (a.side_kind == BDA_SIDE_Q) {
+        for (int s = blockIdx.y; s < a.d_side; s += gridDim.y)
+            for (int i = t; i < n; i += kPrepThreads) {
+                double acc = 0.0;
+                for (int j = 0; j < n; ++j)
+                    acc = fma(load_as_double<WT>(a.side, (int64_t)s * a.ld_side + col0 + j),
+                              load_as_double<WT>(a.W, (int64_t)(off + i) * a.ldw + col0 + j), acc);
+                store_rounded<CT>(a.side_out, (int64_t)s * a.ld_side_out + col0 + i, acc);
+            }
+    } else {
+        for (int i = blockIdx.y; i < n; i += gridDim.y)
+            for (int m = t; m < a.d_side; m += kPrepThreads) {
+                double acc = 0.0;
+                for (int j = 0; j < n; ++j)
+                    acc = fma(load_as_double<WT>(a.W, (int64_t)(off + i) * a.ldw + col0 + j),
+                              load_as_double<WT>(a.side, (col0 + j) * a.ld_side + m), acc);
+                store_rounded<CT>(a.side_out, (col0 + i) * a.ld_side_out + m, acc);
+            }
+    }
+}
+
+// Sum of squared reconstruction errors of the stored form of head blockIdx.x over the rows
+// blockIdx.y, + gridDim.y, ... of the matrix the residual is defined on (Chat = C as stored, Bhat =
+// the companion output as stored, kk = index of row / column k among those outside the window):
+//   no companion   W_h[Bbar,:] - Chat A                                       rows kk
+//   Q              W_q^h W_h^T - [Bhat at the window columns, Bhat Chat^T]    rows s of W_q
+//   O              W_h W_o^h - [Bhat at the window rows; Chat Bhat]           rows k of W_h
+// Each thread sums its elements in a fixed order, the workgroup adds the 256 sums in thread order.
+template <typename WT, typename CT>
+__global__ __launch_bounds__(kPrepThreads) void residual_kernel(const PrepArgs a)
+{
+    __shared__ double red[kPrepThreads];
+    const int n = a.d_h, h = blockIdx.x, t = threadIdx.x, d_c = a.d_c, K = d_c - n;
+    const int off = window_start(a);
+    const int64_t col0 = (int64_t)h * n;
+    auto w = [&](int k, int j) { return load_as_double<WT>(a.W, (int64_t)k * a.ldw + col0 + j); };
+    auto chat = [&](int kk, int i) { return load_as_double<CT>(a.C, (int64_t)kk * a.ldC + col0 + i); };
+    double r2 = 0.0;
+    if (off >= 0) {
+        if (a.side_kind == BDA_SIDE_Q) {
+            for (int s = blockIdx.y; s < a.d_side; s += gridDim.y)
+                for (int k = t; k < d_c; k += kPrepThreads) {
+                    double m = 0.0;
+                    for (int j = 0; j < n; ++j) m = fma(load_as_double<WT>(a.side, (int64_t)s * a.ld_side + col0 + j), w(k, j), m);
+                    double rec;
+                    if (k >= off && k < off + n) {
+                        rec = load_as_double<CT>(a.side_out, (int64_t)s * a.ld_side_out + col0 + (k - off));
+                    } else {
+                        const int kk = k < off ? k : k - n;
+                        rec = 0.0;
+                        for (int i = 0; i < n; ++i) rec = fma(load_as_double<CT>(a.side_out, (int64_t)s * a.ld_side_out + col0 + i), chat(kk, i), rec);
+                    }
+                    const double d = m - rec;
+                    r2 += d * d;
+                }
+        } else if (a.side_kind == BDA_SIDE_O) {
+            for (int k = blockIdx.y; k < d_c; k += gridDim.y)
+                for (int mm = t; mm < a.d_side; mm += kPrepThreads) {
+                    double m = 0.0;
+                    for (int j = 0; j < n; ++j) m = fma(w(k, j), load_as_double<WT>(a.side, (col0 + j) * a.ld_side + mm), m);
+                    double rec;
+                    if (k >= off && k < off + n) {
+                        rec = load_as_double<CT>(a.side_out, (col0 + (k - off)) * a.ld_side_out + mm);
+                    } else {
+                        const int kk = k < off ? k : k - n;
+                        rec = 0.0;
+                        for (int i = 0; i < n; ++i) rec = fma(chat(kk, i), load_as_double<CT>(a.side_out, (col0 + i) * a.ld_side_out + mm), rec);
+                    }
+                    const double d = m - rec;
+                    r2 += d * d;
+                }
+        } else {
+            for (int kk = blockIdx.y; kk < K; kk += gridDim.y)
+                for (int j = t; j < n; j += kPrepThreads) {
+                    double rec = 0.0;
+                    for (int i = 0; i < n; ++i) rec = fma(chat(kk, i), w(off + i, j), rec);
+                    const double d = w(kk < off ? kk : kk + n, j) - rec;
+                    r2 += d * d;
+                }
+        }
+    }
+    red[t] = r2;
+    __syncthreads();
+    if (t == 0) {
+        double s = 0.0;
+        for (int i = 0; i < kPrepThreads; ++i) s += red[i];
+        a.partials[((size_t)a.cand * a.H + h) * a.n_parts + blockIdx.y] = s;
+    }
+}
+
+struct SelectArgs {
+    const double* partials;
+    const int* cand_singular;
+    int* basis_offset_out;
+    double* resid_out;           // NULL or 3 doubles: first window, last window, chosen window
+    int n_cand, H, n_parts, d_c, d_h;
+    int offs[kMaxCandidates];
+};
+
+// One thread: the candidates in order, the heads in order, the parts in order.
+__global__ void select_kernel(const SelectArgs a)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const double inf = __builtin_huge_val(), nan = __builtin_nan("");
+    double best = inf, r_first = nan, r_last = nan;
+    int best_off = -1;
+    for (int ci = 0; ci < a.n_cand; ++ci) {
+        const bool singular = a.cand_singular[ci] != 0;
+        double mean = 0.0;
+        if (a.partials) {
+            for (int h = 0; h < a.H; ++h) {
+                double s = 0.0;
+                for (int p = 0; p < a.n_parts; ++p) s += a.partials[((size_t)ci * a.H + h) * a.n_parts + p];
+                mean += sqrt(s);
+            }
+            mean /= a.H;
+        }
+        if (singular || mean != mean) mean = inf;
+        if (a.offs[ci] == 0) r_first = mean;
+        if (a.offs[ci] == a.d_c - a.d_h) r_last = mean;
+        const bool take = best_off < 0 ? !singular : mean < best;
+        if (take) { best = mean; best_off = a.offs[ci]; }
+    }
+    *a.basis_offset_out = best_off;
+    if (a.resid_out) { a.resid_out[0] = r_first; a.resid_out[1] = r_last; a.resid_out[2] = best; }
+}
+
+__global__ void fill_int_kernel(int* p, int n, int v)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+int check_launch(const char* what)
+{
+    const hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "bda_prepare_device: %s: %s", what, hipGetErrorString(err));
+}
+
+template <typename WT, typename CT>
+int launch_prepare(PrepArgs a, int batch, hipStream_t st)
 {
     const int n = a.d_h;
-    const size_t lds = ((size_t)n * (n + 1) + (size_t)(kPrepRows * n > kPrepThreads ? kPrepRows * n : kPrepThreads)) * sizeof(double);
-    auto kern = prepare_kernel<WT, CT>;
-    hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const bool big = n > kPrepLdsDh;
+    const size_t stage = (size_t)(kPrepRows * n > kPrepThreads ? kPrepRows * n : kPrepThreads);
+    const size_t lds = ((big ? 0 : (size_t)n * (n + 1)) + stage) * sizeof(double);
+    const void* kern = big ? (const void*)prepare_kernel<WT, CT, true> : (const void*)prepare_kernel<WT, CT, false>;
+    hipError_t err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return fail(BDA_EHIP, "bda_prepare_device: LDS size %zu: %s", lds, hipGetErrorString(err));
-    hipLaunchKernelGGL(kern, dim3(a.H), dim3(kPrepThreads), lds, st, a);
-    err = hipGetLastError();
-    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "bda_prepare_device: kernel launch: %s", hipGetErrorString(err));
+    const int per_launch = big ? batch : a.H;
+    for (int h0 = 0; h0 < a.H; h0 += per_launch) {
+        a.h0 = h0;
+        const int heads = a.H - h0 < per_launch ? a.H - h0 : per_launch;
+        if (big) hipLaunchKernelGGL((prepare_kernel<WT, CT, true>), dim3(heads), dim3(kPrepThreads), lds, st, a);
+        else hipLaunchKernelGGL((prepare_kernel<WT, CT, false>), dim3(heads), dim3(kPrepThreads), lds, st, a);
+        if (int rc = check_launch("prepare kernel")) return rc;
+    }
+    return BDA_OK;
+}
+
+// What a call needs beyond its inputs and outputs, and where it lies in the workspace.
+struct Plan {
+    int n_cand, n_parts, batch;
+    bool want_resid, big;
+    size_t flags_bytes, partial_bytes, mat_bytes_per_head;
+    int offs[kMaxCandidates];
+};
+
+int make_plan(const char* fn, int d_c, int H, int d_h, int mode, int explicit_offset, bool resid_wanted, Plan& p)
+{
+    const int last = d_c - d_h;
+    p.n_cand = 0;
+    switch (mode) {
+    case BDA_BASIS_FIRST: p.offs[p.n_cand++] = 0; break;
+    case BDA_BASIS_LAST: p.offs[p.n_cand++] = last; break;
+    case BDA_BASIS_RESIDUAL_MIN: p.offs[p.n_cand++] = 0; p.offs[p.n_cand++] = last; break;
+    case BDA_BASIS_OFFSET_SEARCH:
+        if (last / 16 + 2 > kMaxCandidates) return fail(BDA_EINVAL, "%s: more than %d candidate windows", fn, kMaxCandidates);
+        for (int o = 0; o <= last; o += 16) p.offs[p.n_cand++] = o;
+        if (last % 16) p.offs[p.n_cand++] = last;
+        break;
+    case BDA_BASIS_EXPLICIT:
+        if (explicit_offset < 0 || explicit_offset > last) return fail(BDA_EINVAL, "%s: basis_offset %d outside [0, %d]", fn, explicit_offset, last);
+        p.offs[p.n_cand++] = explicit_offset;
+        break;
+    default: return fail(BDA_EINVAL, "%s: bad basis mode %d", fn, mode);
+    }
+    p.want_resid = p.n_cand > 1 || resid_wanted;
+    p.big = d_h > kPrepLdsDh;
+    int parts = 1024 / H;
+    p.n_parts = parts < 1 ? 1 : parts > kMaxParts ? kMaxParts : parts;
+    p.flags_bytes = kMaxCandidates * sizeof(int);
+    p.partial_bytes = p.want_resid ? (((size_t)p.n_cand * H * p.n_parts * sizeof(double) + 255) & ~(size_t)255) : 0;
+    p.mat_bytes_per_head = p.big ? (size_t)d_h * d_h * sizeof(double) : 0;
+    p.batch = 0;
+    return BDA_OK;
+}
+
+struct PrepCall {
+    const void* W; int64_t ldw; int w_dtype; int d_c, H, d_h;
+    const void* side; int64_t ld_side; int d_side; int side_kind;
+    int mode, explicit_offset;
+    void* C; int64_t ldC; void* side_out; int64_t ld_side_out; int c_dtype;
+    int* basis_offset_out; double* resid_out; int* singular_head;
+};
+
+template <typename WT, typename CT>
+int run_prepare(const PrepCall& c, const Plan& p, unsigned char* ws, hipStream_t st)
+{
+    int* flags = (int*)ws;
+    double* partials = p.want_resid ? (double*)(ws + p.flags_bytes) : nullptr;
+    double* mat = p.big ? (double*)(ws + p.flags_bytes + p.partial_bytes) : nullptr;
+    PrepArgs a{};
+    a.W = c.W; a.side = c.side; a.C = c.C; a.side_out = c.side_out;
+    a.status = c.singular_head;
+    a.cand_singular = ws ? flags : nullptr;
+    a.partials = partials; a.mat = mat;
+    a.ldw = c.ldw; a.ld_side = c.ld_side; a.ldC = c.ldC; a.ld_side_out = c.ld_side_out;
+    a.d_c = c.d_c; a.H = c.H; a.d_h = c.d_h; a.d_side = c.d_side; a.side_kind = c.side_kind;
+    a.n_parts = p.n_parts;
+    const bool multi = p.n_cand > 1;
+    const int side_parts = c.side_kind == BDA_SIDE_Q ? (c.d_side < 64 ? c.d_side : 64) : (c.d_h < 64 ? c.d_h : 64);
+    if (ws) {
+        hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(kMaxCandidates), 0, st, flags, kMaxCandidates, 0);
+        if (int rc = check_launch("fill kernel")) return rc;
+    }
+    for (int ci = 0; ci < p.n_cand; ++ci) {
+        a.off = p.offs[ci];
+        a.off_ptr = nullptr;
+        a.cand = ci;
+        a.status = multi ? nullptr : c.singular_head;      // during a search a singular window is just a bad candidate
+        if (int rc = launch_prepare<WT, CT>(a, p.batch, st)) return rc;
+        if (c.side_kind != BDA_SIDE_NONE) {
+            hipLaunchKernelGGL((side_kernel<WT, CT>), dim3(c.H, side_parts), dim3(kPrepThreads), 0, st, a);
+            if (int rc = check_launch("companion kernel")) return rc;
+        }
+        if (p.want_resid) {
+            hipLaunchKernelGGL((residual_kernel<WT, CT>), dim3(c.H, p.n_parts), dim3(kPrepThreads), 0, st, a);
+            if (int rc = check_launch("residual kernel")) return rc;
+        }
+    }
+    if (p.want_resid) {
+        SelectArgs s{};
+        s.partials = partials; s.cand_singular = flags; s.basis_offset_out = c.basis_offset_out; s.resid_out = c.resid_out;
+        s.n_cand = p.n_cand; s.H = c.H; s.n_parts = p.n_parts; s.d_c = c.d_c; s.d_h = c.d_h;
+        for (int i = 0; i < p.n_cand; ++i) s.offs[i] = p.offs[i];
+        hipLaunchKernelGGL(select_kernel, dim3(1), dim3(64), 0, st, s);
+        if (int rc = check_launch("select kernel")) return rc;
+    } else if (c.basis_offset_out) {
+        hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(64), 0, st, c.basis_offset_out, 1, p.offs[0]);
+        if (int rc = check_launch("fill kernel")) return rc;
+    }
+    if (multi) {
+        // the chosen window once more, into the outputs for good (its start is read on the device)
+        a.off = -1;
+        a.off_ptr = c.basis_offset_out;
+        a.cand = 0;
+        a.cand_singular = nullptr;
+        a.status = c.singular_head;
+        if (int rc = launch_prepare<WT, CT>(a, p.batch, st)) return rc;
+        if (c.side_kind != BDA_SIDE_NONE) {
+            hipLaunchKernelGGL((side_kernel<WT, CT>), dim3(c.H, side_parts), dim3(kPrepThreads), 0, st, a);
+            if (int rc = check_launch("companion kernel")) return rc;
+        }
+    }
+    return BDA_OK;
 }
 
 template <typename WT>
-int dispatch_c(const PrepArgs& a, int c_dtype, hipStream_t st)
+int dispatch_c(const PrepCall& c, const Plan& p, unsigned char* ws, hipStream_t st)
 {
-    switch (c_dtype) {
-    case BDA_F64: return launch_prepare<WT, double>(a, st);
-    case BDA_F32: return launch_prepare<WT, float>(a, st);
-    case BDA_F16: return launch_prepare<WT, _Float16>(a, st);
-    case BDA_BF16: return launch_prepare<WT, __bf16>(a, st);
-    default: return fail(BDA_EDTYPE, "bda_prepare_device: bad c_dtype %d", c_dtype);
+    switch (c.c_dtype) {
+    case BDA_F64: return run_prepare<WT, double>(c, p, ws, st);
+    case BDA_F32: return run_prepare<WT, float>(c, p, ws, st);
+    case BDA_F16: return run_prepare<WT, _Float16>(c, p, ws, st);
+    case BDA_BF16: return run_prepare<WT, __bf16>(c, p, ws, st);
+    default: return fail(BDA_EDTYPE, "bda_prepare_device: bad c_dtype %d", c.c_dtype);
     }
+}
+
+int dispatch_w(const PrepCall& c, const Plan& p, unsigned char* ws, hipStream_t st)
+{
+    switch (c.w_dtype) {
+    case BDA_F64: return dispatch_c<double>(c, p, ws, st);
+    case BDA_F32: return dispatch_c<float>(c, p, ws, st);
+    case BDA_F16: return dispatch_c<_Float16>(c, p, ws, st);
+    case BDA_BF16: return dispatch_c<__bf16>(c, p, ws, st);
+    default: return fail(BDA_EDTYPE, "bda_prepare_device: bad w_dtype %d", c.w_dtype);
+    }
+}
+
+// Argument checks shared by the entry points; fills the plan (without the batch size).
+int check_call(const char* fn, const PrepCall& c, Plan& p)
+{
+    if (!c.W || !c.C) return fail(BDA_EINVAL, "%s: NULL W or C", fn);
+    if (c.d_h <= 0 || c.d_c <= c.d_h || c.H <= 0) return fail(BDA_EINVAL, "%s: need 0 < d_h < d_c and H > 0", fn);
+    if (c.d_h > kPrepMaxDh) return fail(BDA_EINVAL, "%s: d_h = %d exceeds %d (use bda_prepare)", fn, c.d_h, kPrepMaxDh);
+    const int64_t N = (int64_t)c.H * c.d_h;
+    if (c.ldw < N || c.ldC < N) return fail(BDA_EINVAL, "%s: leading dimension smaller than H d_h = %lld", fn, (long long)N);
+    if (c.side_kind != BDA_SIDE_NONE) {
+        if (c.side_kind != BDA_SIDE_Q && c.side_kind != BDA_SIDE_O) return fail(BDA_EINVAL, "%s: bad side_kind %d", fn, c.side_kind);
+        if (!c.side || !c.side_out || c.d_side <= 0) return fail(BDA_EINVAL, "%s: companion asked for but side or side_out NULL or d_side <= 0", fn);
+        const int64_t need = c.side_kind == BDA_SIDE_Q ? N : c.d_side;
+        if (c.ld_side < need || c.ld_side_out < need) return fail(BDA_EINVAL, "%s: companion leading dimension too small (need %lld)", fn, (long long)need);
+    }
+    if (int rc = make_plan(fn, c.d_c, c.H, c.d_h, c.mode, c.explicit_offset, c.resid_out != nullptr, p)) return rc;
+    if ((p.n_cand > 1 || c.resid_out) && !c.basis_offset_out) return fail(BDA_EINVAL, "%s: basis_offset_out is NULL", fn);
+    return BDA_OK;
+}
+
+// Workspace bytes of a call: the flags, the residual partial sums, and (d_h > 128) `batch` basis blocks.
+size_t workspace_need(const Plan& p, int batch) { return p.flags_bytes + p.partial_bytes + p.mat_bytes_per_head * (size_t)batch; }
+
+int run_with_workspace(const char* fn, const PrepCall& c, Plan& p, void* workspace, size_t workspace_bytes, hipStream_t st)
+{
+    const bool needs = p.want_resid || p.big;
+    if (!needs) return dispatch_w(c, p, nullptr, st);
+    const size_t least = workspace_need(p, p.big ? 1 : 0);
+    if (!workspace || workspace_bytes < least)
+        return fail(BDA_EINVAL, "%s: workspace of %zu bytes, this call needs at least %zu", fn, workspace ? workspace_bytes : (size_t)0, least);
+    if ((uintptr_t)workspace % 16) return fail(BDA_EINVAL, "%s: workspace not 16-byte aligned", fn);
+    if (p.big) {
+        const size_t heads = (workspace_bytes - p.flags_bytes - p.partial_bytes) / p.mat_bytes_per_head;
+        p.batch = (int)(heads < (size_t)c.H ? heads : (size_t)c.H);
+    }
+    return dispatch_w(c, p, (unsigned char*)workspace, st);
 }
 
 }  // namespace
@@ -229,24 +596,41 @@ int dispatch_c(const PrepArgs& a, int c_dtype, hipStream_t st)
 
 using namespace bda;
 
+extern "C" size_t bda_prepare_device_workspace_bytes(int d_c, int H, int d_h, bda_basis_mode mode, int want_residuals)
+{
+    clear_error();
+    if (d_h <= 0 || d_c <= d_h || H <= 0 || d_h > kPrepMaxDh) return 0;
+    Plan p;
+    if (make_plan("bda_prepare_device_workspace_bytes", d_c, H, d_h, (int)mode, 0, want_residuals != 0, p)) return 0;
+    if (!p.want_resid && !p.big) return 0;
+    return workspace_need(p, p.big ? (H < 32 ? H : 32) : 0);
+}
+
+extern "C" int bda_prepare_device_ex(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
+                                     const void* side, int64_t ld_side, int d_side, bda_side side_kind,
+                                     bda_basis_mode mode, int explicit_offset,
+                                     void* C, int64_t ldC, void* side_out, int64_t ld_side_out, bda_dtype c_dtype,
+                                     int* basis_offset_out, double* resid_out, int* singular_head,
+                                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    const PrepCall c{W, ldw, (int)w_dtype, d_c, H, d_h, side, ld_side, d_side, side ? (int)side_kind : (int)BDA_SIDE_NONE,
+                     (int)mode, explicit_offset, C, ldC, side_out, ld_side_out, (int)c_dtype,
+                     basis_offset_out, resid_out, singular_head};
+    Plan p;
+    if (int rc = check_call("bda_prepare_device_ex", c, p)) return rc;
+    return run_with_workspace("bda_prepare_device_ex", c, p, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
 extern "C" int bda_prepare_device(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
                                   int basis_offset, void* C, int64_t ldC, bda_dtype c_dtype,
                                   int* singular_head, void* stream)
 {
     clear_error();
-    if (!W || !C) return fail(BDA_EINVAL, "bda_prepare_device: NULL pointer");
-    if (d_h <= 0 || d_c <= d_h || H <= 0) return fail(BDA_EINVAL, "bda_prepare_device: need 0 < d_h < d_c and H > 0");
-    if (d_h > kPrepMaxDh) return fail(BDA_EINVAL, "bda_prepare_device: d_h = %d exceeds %d (use bda_prepare)", d_h, kPrepMaxDh);
-    const int64_t N = (int64_t)H * d_h;
-    if (ldw < N || ldC < N) return fail(BDA_EINVAL, "bda_prepare_device: leading dimension smaller than H d_h = %lld", (long long)N);
-    if (basis_offset < 0 || basis_offset > d_c - d_h) return fail(BDA_EINVAL, "bda_prepare_device: basis_offset %d out of range", basis_offset);
-    PrepArgs a{W, C, singular_head, ldw, ldC, d_c, H, d_h, basis_offset};
-    hipStream_t st = (hipStream_t)stream;
-    switch (w_dtype) {
-    case BDA_F64: return dispatch_c<double>(a, c_dtype, st);
-    case BDA_F32: return dispatch_c<float>(a, c_dtype, st);
-    case BDA_F16: return dispatch_c<_Float16>(a, c_dtype, st);
-    case BDA_BF16: return dispatch_c<__bf16>(a, c_dtype, st);
-    default: return fail(BDA_EDTYPE, "bda_prepare_device: bad w_dtype %d", w_dtype);
-    }
+    if (d_h > kPrepLdsDh) return fail(BDA_EINVAL, "bda_prepare_device: d_h = %d exceeds %d (bda_prepare_device_ex takes a workspace for up to %d)", d_h, kPrepLdsDh, kPrepMaxDh);
+    const PrepCall c{W, ldw, (int)w_dtype, d_c, H, d_h, nullptr, 0, 0, (int)BDA_SIDE_NONE, (int)BDA_BASIS_EXPLICIT, basis_offset,
+                     C, ldC, nullptr, 0, (int)c_dtype, nullptr, nullptr, singular_head};
+    Plan p;
+    if (int rc = check_call("bda_prepare_device", c, p)) return rc;
+    return dispatch_w(c, p, nullptr, (hipStream_t)stream);
 }

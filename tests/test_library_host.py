@@ -170,6 +170,26 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert lib.bda_prepare_device(fake, 512, 3, 1024, 2, 256, 0, fake, 512, 1, None, None) == -1
     assert lib.bda_prepare_device(fake, 32, 7, 64, 2, 16, 0, fake, 32, 1, None, None) == -3
     assert lib.bda_prepare_device(fake, 16, 3, 64, 2, 16, 0, fake, 32, 1, None, None) == -1
+    # the long form: a search needs a workspace (the message says how much), a companion its output, a
+    # search somewhere to put the chosen window; no more than 256 candidate windows; d_h up to 256
+    ex = lib.bda_prepare_device_ex
+    need = lib.bda_prepare_device_workspace_bytes(64, 2, 16, 2, 0)
+    assert need == 1024 + 256 * ((2 * 2 * 16 * 8 + 255) // 256)
+    assert lib.bda_prepare_device_workspace_bytes(64, 2, 16, 0, 0) == 0 and lib.bda_prepare_device_workspace_bytes(64, 2, 64, 0, 0) == 0
+    assert lib.bda_prepare_device_workspace_bytes(1024, 2, 256, 0, 0) == 1024 + 2 * 256 * 256 * 8
+    assert ex(fake, 32, 3, 64, 2, 16, None, 0, 0, 0, 2, 0, fake, 32, None, 0, 1, fake, None, None, None, 0, None) == -1
+    assert str(need).encode() in lib.bda_last_error()
+    assert ex(fake, 32, 3, 64, 2, 16, None, 0, 0, 0, 2, 0, fake, 32, None, 0, 1, fake, None, None, fake, need - 1, None) == -1
+    assert ex(fake, 32, 3, 64, 2, 16, None, 0, 0, 0, 2, 0, fake, 32, None, 0, 1, None, None, None, fake, need, None) == -1
+    assert b"basis_offset_out" in lib.bda_last_error()
+    assert ex(fake, 32, 3, 64, 2, 16, fake, 32, 8, 1, 0, 0, fake, 32, None, 32, 1, None, None, None, None, 0, None) == -1
+    assert b"companion" in lib.bda_last_error()
+    assert ex(fake, 32, 3, 64, 2, 16, fake, 16, 8, 1, 0, 0, fake, 32, fake, 32, 1, None, None, None, None, 0, None) == -1
+    assert ex(fake, 16, 3, 8192, 1, 16, None, 0, 0, 0, 3, 0, fake, 16, None, 0, 1, fake, None, None, fake, 1 << 30, None) == -1
+    assert b"candidate" in lib.bda_last_error()
+    assert ex(fake, 1028, 3, 1024, 4, 257, None, 0, 0, 0, 0, 0, fake, 1028, None, 0, 1, None, None, None, None, 0, None) == -1
+    assert ex(fake, 512, 3, 1024, 2, 256, None, 0, 0, 0, 0, 0, fake, 512, None, 0, 1, None, None, None, None, 0, None) == -1   # d_h > 128 needs a workspace
+    assert ex(fake, 32, 3, 64, 2, 16, None, 0, 0, 0, 9, 0, fake, 32, None, 0, 1, None, None, None, None, 0, None) == -1
     # gradients: bad window, ld too small, a gradient on top of an input, grad dtype, nothing asked for
     far = ctypes.c_void_p(0x900000)
     farther = ctypes.c_void_p(0xA00000)
