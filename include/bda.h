@@ -150,6 +150,24 @@ int bda_prepare_device_ex(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * bda_prepare_device_ex for callers that cannot allocate device memory and have no workspace to pass
+ * (code under HIP graph capture, serving loops, harnesses that forbid hipMalloc): same arguments without
+ * the workspace, same kernels, same results.  The call's partial results live in a fixed 8 MiB array
+ * that is part of the library's device code: every GPU the library runs on holds it from the moment the
+ * library's code is loaded there until the process ends.  The call allocates and frees nothing.
+ * Limits: what bda_prepare_device_ex would need with one basis block (1 KiB + 8 bytes x candidate windows
+ * x H x min(16, 1024 / H) + 8 d_h^2 for d_h > 128) must fit the 8 MiB; beyond that the call fails with
+ * BDA_EINVAL and a message that names both sizes.  For d_h > 128 as many heads are prepared per launch as
+ * basis blocks fit the rest of the array.  Every call on a GPU shares that GPU's array (it clears what it
+ * needs cleared): calls that overlap on one GPU - two streams, two threads - race; keep them in order.
+ */
+int bda_prepare_device_static(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
+                              const void* side, int64_t ld_side, int d_side, bda_side side_kind,
+                              bda_basis_mode mode, int explicit_offset,
+                              void* C, int64_t ldC, void* side_out, int64_t ld_side_out, bda_dtype c_dtype,
+                              int* basis_offset_out, double* resid_out, int* singular_head, void* stream);
+
+/*
  * The short form: C only, for an explicit window (0 = first, d_c - d_h = last, or the offset a search
  * returned), d_h <= 128, no workspace.  Arguments as above.
  */

@@ -19,7 +19,7 @@ BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
 EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_prepare_device_ex",
-           "bda_prepare_device_workspace_bytes", "bda_kv_project", "bda_dense_project",
+           "bda_prepare_device_workspace_bytes", "bda_prepare_device_static", "bda_kv_project", "bda_dense_project",
            "bda_lowrank_linear", "bda_kv_project_backward", "bda_kv_project_ex", "bda_dense_project_ex",
            "bda_kv_project_backward_ex", "bda_kv_project_plan", "bda_dense_project_plan", "bda_last_error", "bda_version")
 
@@ -76,6 +76,9 @@ def load():
     lib.bda_prepare_device_ex.restype = c_int
     lib.bda_prepare_device_ex.argtypes = [vp, i64, c_int, c_int, c_int, c_int, vp, i64, c_int, c_int, c_int, c_int,
                                           vp, i64, vp, i64, c_int, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.bda_prepare_device_static.restype = c_int
+    lib.bda_prepare_device_static.argtypes = [vp, i64, c_int, c_int, c_int, c_int, vp, i64, c_int, c_int, c_int, c_int,
+                                              vp, i64, vp, i64, c_int, vp, vp, vp, vp]
     lib.bda_kv_project.restype = c_int
     lib.bda_kv_project.argtypes = [vp, i64, i64, c_int, c_int, c_int, ip, ip, vp, i64, vp, i64,
                                    c_int, c_int, vp]
@@ -232,6 +235,17 @@ def bda_prepare_device_ex(W, ldw: int, w_dtype: int, d_c: int, H: int, d_h: int,
                                      mode, explicit_offset, _ptr(C), ldC, _ptr(side_out), ld_side_out, c_dtype,
                                      _ptr(basis_offset_out), _ptr(resid_out), _ptr(singular_head),
                                      _ptr(workspace), int(workspace_bytes), stream or None))
+
+
+def bda_prepare_device_static(W, ldw: int, w_dtype: int, d_c: int, H: int, d_h: int, C, ldC: int, c_dtype: int,
+                              side=None, ld_side: int = 0, d_side: int = 0, side_kind: int = SIDE_NONE,
+                              side_out=None, ld_side_out: int = 0, mode: int = BASIS_FIRST, explicit_offset: int = 0,
+                              basis_offset_out=None, resid_out=None, singular_head=None, stream: int = 0) -> None:
+    """bda_prepare_device_ex without a workspace (the library's built-in scratch); see include/bda.h."""
+    lib = load()
+    _check(lib.bda_prepare_device_static(_ptr(W), ldw, w_dtype, d_c, H, d_h, _ptr(side), ld_side, d_side, side_kind,
+                                         mode, explicit_offset, _ptr(C), ldC, _ptr(side_out), ld_side_out, c_dtype,
+                                         _ptr(basis_offset_out), _ptr(resid_out), _ptr(singular_head), stream or None))
 
 
 def bda_dense_project(c, ldc: int, T: int, d_c: int, W, ldW: int, N: int, out, ld_out: int,

@@ -21,8 +21,16 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 
 #include "bda_internal.h"
+
+// Scratch memory of bda_prepare_device_static, the entry point for callers that cannot allocate: part of
+// the code object, so every GPU the library runs on holds its own copy from the moment the code is loaded
+// there until the process ends.  Host code never uses this name as an address: it asks the runtime for
+// the array's address on the current device (static_scratch below) and passes that to the kernels.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace bda {
 namespace {
@@ -591,6 +599,27 @@ int run_with_workspace(const char* fn, const PrepCall& c, Plan& p, void* workspa
     return dispatch_w(c, p, (unsigned char*)workspace, st);
 }
 
+// Address of the static scratch array on the current device; looked up once per device.
+int static_scratch(const char* fn, unsigned char** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return fail(BDA_EHIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(err));
+    if (dev < 0 || dev >= kMaxDevices) return fail(BDA_EINVAL, "%s: device index %d beyond %d", fn, dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !p) return fail(BDA_EHIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(err));
+        ptrs[dev] = p;
+    }
+    *out = (unsigned char*)ptrs[dev];
+    return BDA_OK;
+}
+
 }  // namespace
 }  // namespace bda
 
@@ -633,4 +662,27 @@ extern "C" int bda_prepare_device(const void* W, int64_t ldw, bda_dtype w_dtype,
     Plan p;
     if (int rc = check_call("bda_prepare_device", c, p)) return rc;
     return dispatch_w(c, p, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int bda_prepare_device_static(const void* W, int64_t ldw, bda_dtype w_dtype, int d_c, int H, int d_h,
+                                         const void* side, int64_t ld_side, int d_side, bda_side side_kind,
+                                         bda_basis_mode mode, int explicit_offset,
+                                         void* C, int64_t ldC, void* side_out, int64_t ld_side_out, bda_dtype c_dtype,
+                                         int* basis_offset_out, double* resid_out, int* singular_head, void* stream)
+{
+    clear_error();
+    const char* fn = "bda_prepare_device_static";
+    const PrepCall c{W, ldw, (int)w_dtype, d_c, H, d_h, side, ld_side, d_side, side ? (int)side_kind : (int)BDA_SIDE_NONE,
+                     (int)mode, explicit_offset, C, ldC, side_out, ld_side_out, (int)c_dtype,
+                     basis_offset_out, resid_out, singular_head};
+    Plan p;
+    if (int rc = check_call(fn, c, p)) return rc;
+    if (!p.want_resid && !p.big) return dispatch_w(c, p, nullptr, (hipStream_t)stream);
+    const size_t least = workspace_need(p, p.big ? 1 : 0);
+    if (least > kStaticScratchBytes)
+        return fail(BDA_EINVAL, "%s: this call needs %zu bytes of scratch, the built-in scratch holds %zu: use bda_prepare_device_ex with a workspace",
+                    fn, least, kStaticScratchBytes);
+    unsigned char* ws = nullptr;
+    if (int rc = static_scratch(fn, &ws)) return rc;
+    return run_with_workspace(fn, c, p, ws, kStaticScratchBytes, (hipStream_t)stream);
 }
