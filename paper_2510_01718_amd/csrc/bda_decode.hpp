@@ -421,11 +421,11 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in
         }
     const int n_idv = p.ident ? 4 * TPW : 0;
 
-    f32x16 acc[TPW];
+    f32x16 acc[TPW], acc2[TPW];                           // even and odd k-steps
 #pragma unroll
     for (int tbl = 0; tbl < TPW; ++tbl)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[tbl][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc[tbl][r] = acc2[tbl][r] = 0.0f;
 
     // transposing-read address: 16-lane group gq, s = lane % 16: row 8 lhi + s / 4 (+ 4 for the second
     // read), columns 32 wc + 16 (gq & 1) + 4 (s & 3) .. + 3
@@ -449,18 +449,37 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in
         const int later = issued - RPC * (c + 1);
         wait_vmcnt_at_most((later > 0 ? later : 0) + n_idv);
         __syncthreads();
-        const int ks_end = nks < CH * (c + 1) ? nks : CH * (c + 1);
-        for (int ks = CH * c; ks < ks_end; ++ks) {       // (a plain loop: the accumulators stay where they are)
+        // the chunk's fragments first (eighteen reads in flight together), then its MFMAs; a k-step past K
+        // multiplies zeros; the k-steps alternate between two accumulators per token block, which halves
+        // the chain of dependent MFMAs
+        u32x4 fw[CH], ft[CH][TPW];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const bool ok = CH * c + i < nks;
+            const int ks = ok ? CH * c + i : nks - 1;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * (16 * ROW_B)));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(smem + w_rd + ks * (16 * ROW_B) + 4 * ROW_B));
             const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-            const u32x4 fw = {lo2[0], lo2[1], hi2[0], hi2[1]};
+            fw[i] = (u32x4){lo2[0], lo2[1], hi2[0], hi2[1]};
             const uint32_t ta = (t_rd + (uint32_t)((ks >> 2) * (NTB * 4096))) ^ (uint32_t)((ks & 3) << 5);
 #pragma unroll
-            for (int tbl = 0; tbl < TPW; ++tbl)            // (blocks past T hold zeros)
-                acc[tbl] = X::mfma(fw, *(lds_u32x4)(uintptr_t)(ta + tbl * 4096), acc[tbl]);
+            for (int tbl = 0; tbl < TPW; ++tbl) {          // (blocks past T hold zeros)
+                const u32x4 t = *(lds_u32x4)(uintptr_t)(ta + tbl * 4096);
+                ft[i][tbl] = ok ? t : (u32x4){0u, 0u, 0u, 0u};
+            }
         }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+#pragma unroll
+            for (int tbl = 0; tbl < TPW; ++tbl) {
+                if (i & 1) acc2[tbl] = X::mfma(fw[i], ft[i][tbl], acc2[tbl]);
+                else acc[tbl] = X::mfma(fw[i], ft[i][tbl], acc[tbl]);
+            }
     }
+#pragma unroll
+    for (int tbl = 0; tbl < TPW; ++tbl)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[tbl][r] += acc2[tbl][r];
 
     // ---- epilogue: lane (token l31, half lhi) holds columns 32 wc + 8 q + 4 lhi + 0..3, q = 0..3 -----
     const __amdgpu_buffer_rsrc_t rD = make_rsrc((char*)p.D + n0 * (int64_t)sizeof(OutT),
