@@ -44,12 +44,15 @@ namespace bda {
 // again by this kernel; streaming it keeps the latent and weight tiles in the L2.
 constexpr int kStreamStoreAux = 2;
 
-// s_waitcnt vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt = [15:14|3:0]).
+// s_waitcnt vmcnt(n) with the other counters left alone.  Issued as volatile assembly with a memory
+// clobber: the count includes loads the compiler issues for builtins (token fragments, identity
+// values) next to the DMA requests written in assembly, so no memory access may be moved across the
+// wait in either direction - it is the program order at this point that the count was made for.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is six bits");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
 // N (2 or 4) LDS DMA loads of 16 bytes per lane through one descriptor; the LDS image of load j
