@@ -292,62 +292,107 @@ __global__ __launch_bounds__(kPrepThreads) void side_kernel(const PrepArgs a)
     }
 }
 
-// Sum of squared reconstruction errors of the stored form of head blockIdx.x over the rows
-// blockIdx.y, + gridDim.y, ... of the matrix the residual is defined on (Chat = C as stored, Bhat =
+// Sum of squared reconstruction errors of the stored form of head blockIdx.x (Chat = C as stored, Bhat =
 // the companion output as stored, kk = index of row / column k among those outside the window):
-//   no companion   W_h[Bbar,:] - Chat A                                       rows kk
-//   Q              W_q^h W_h^T - [Bhat at the window columns, Bhat Chat^T]    rows s of W_q
-//   O              W_h W_o^h - [Bhat at the window rows; Chat Bhat]           rows k of W_h
-// Each thread sums its elements in a fixed order, the workgroup adds the 256 sums in thread order.
+//   no companion   W_h[Bbar,:] - Chat A                                       (d_c - d_h) x d_h
+//   Q              W_q^h W_h^T - [Bhat at the window columns, Bhat Chat^T]    d_side x d_c
+//   O              W_h W_o^h - [Bhat at the window rows; Chat Bhat]           d_c x d_side
+// In every case an element is  P1(r, c) - P2(r, c) - S(r, c)  with two products over the head width, of
+// which one or the other (or S) is absent for some rows or columns.  The matrix is cut into 64 x 64
+// tiles; workgroup (head, part) takes tiles part, part + gridDim.y, ...; the operands of a tile are
+// staged through LDS 16 columns of the contraction at a time and every thread owns a 4 x 4 sub-grid
+// of the tile (rows ty + 16 u, columns tx + 16 v).  Each thread adds its squares in a fixed order, the
+// workgroup adds the 256 sums in thread order: the result does not depend on scheduling.
 template <typename WT, typename CT>
 __global__ __launch_bounds__(kPrepThreads) void residual_kernel(const PrepArgs a)
 {
+    constexpr int TS = 64, KC = 16;
+    __shared__ double As[TS][KC + 1];
+    __shared__ double Bs[KC][TS + 1];
     __shared__ double red[kPrepThreads];
     const int n = a.d_h, h = blockIdx.x, t = threadIdx.x, d_c = a.d_c, K = d_c - n;
     const int off = window_start(a);
     const int64_t col0 = (int64_t)h * n;
+    const int kind = a.side_kind;
+    const int R = kind == BDA_SIDE_Q ? a.d_side : kind == BDA_SIDE_O ? d_c : K;
+    const int Cn = kind == BDA_SIDE_Q ? d_c : kind == BDA_SIDE_O ? a.d_side : n;
     auto w = [&](int k, int j) { return load_as_double<WT>(a.W, (int64_t)k * a.ldw + col0 + j); };
     auto chat = [&](int kk, int i) { return load_as_double<CT>(a.C, (int64_t)kk * a.ldC + col0 + i); };
+    auto in_window = [&](int k) { return k >= off && k < off + n; };
+    auto outside_index = [&](int k) { return k < off ? k : k - n; };
+    // first product: P1(r, c) = sum_j a1(r, j) b1(j, c)
+    auto a1 = [&](int r, int j) -> double {
+        if (r >= R) return 0.0;
+        if (kind == BDA_SIDE_Q) return load_as_double<WT>(a.side, (int64_t)r * a.ld_side + col0 + j);
+        if (kind == BDA_SIDE_O) return w(r, j);
+        return 0.0;
+    };
+    auto b1 = [&](int j, int c) -> double {
+        if (c >= Cn) return 0.0;
+        if (kind == BDA_SIDE_Q) return w(c, j);
+        if (kind == BDA_SIDE_O) return load_as_double<WT>(a.side, (col0 + j) * a.ld_side + c);
+        return 0.0;
+    };
+    // second product: P2(r, c) = sum_i a2(r, i) b2(i, c), absent at the window's columns (Q) / rows (O)
+    auto a2 = [&](int r, int i) -> double {
+        if (r >= R) return 0.0;
+        if (kind == BDA_SIDE_Q) return load_as_double<CT>(a.side_out, (int64_t)r * a.ld_side_out + col0 + i);
+        if (kind == BDA_SIDE_O) return in_window(r) ? 0.0 : chat(outside_index(r), i);
+        return chat(r, i);
+    };
+    auto b2 = [&](int i, int c) -> double {
+        if (c >= Cn) return 0.0;
+        if (kind == BDA_SIDE_Q) return in_window(c) ? 0.0 : chat(outside_index(c), i);
+        if (kind == BDA_SIDE_O) return load_as_double<CT>(a.side_out, (col0 + i) * a.ld_side_out + c);
+        return w(off + i, c);
+    };
+    // what stands alone: minus Bhat at the window (Q, O); plus the row of W_h itself (no companion)
+    auto lone = [&](int r, int c) -> double {
+        if (r >= R || c >= Cn) return 0.0;
+        if (kind == BDA_SIDE_Q) return in_window(c) ? -load_as_double<CT>(a.side_out, (int64_t)r * a.ld_side_out + col0 + (c - off)) : 0.0;
+        if (kind == BDA_SIDE_O) return in_window(r) ? -load_as_double<CT>(a.side_out, (col0 + (r - off)) * a.ld_side_out + c) : 0.0;
+        return w(r < off ? r : r + n, c);
+    };
+    const int tx = t % 16, ty = t / 16;
+    const int tiles_c = (Cn + TS - 1) / TS, n_tiles = ((R + TS - 1) / TS) * tiles_c;
     double r2 = 0.0;
     if (off >= 0) {
-        if (a.side_kind == BDA_SIDE_Q) {
-            for (int s = blockIdx.y; s < a.d_side; s += gridDim.y)
-                for (int k = t; k < d_c; k += kPrepThreads) {
-                    double m = 0.0;
-                    for (int j = 0; j < n; ++j) m = fma(load_as_double<WT>(a.side, (int64_t)s * a.ld_side + col0 + j), w(k, j), m);
-                    double rec;
-                    if (k >= off && k < off + n) {
-                        rec = load_as_double<CT>(a.side_out, (int64_t)s * a.ld_side_out + col0 + (k - off));
-                    } else {
-                        const int kk = k < off ? k : k - n;
-                        rec = 0.0;
-                        for (int i = 0; i < n; ++i) rec = fma(load_as_double<CT>(a.side_out, (int64_t)s * a.ld_side_out + col0 + i), chat(kk, i), rec);
+        for (int tile = blockIdx.y; tile < n_tiles; tile += gridDim.y) {
+            const int r0 = (tile / tiles_c) * TS, c0 = (tile % tiles_c) * TS;
+            double acc[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+            for (int pass = (kind == BDA_SIDE_NONE ? 1 : 0); pass < 2; ++pass) {
+                for (int j0 = 0; j0 < n; j0 += KC) {
+                    for (int e = t; e < TS * KC; e += kPrepThreads) {
+                        const int rr = e / KC, jj = e % KC;
+                        const bool ok = j0 + jj < n;
+                        As[rr][jj] = !ok ? 0.0 : pass == 0 ? a1(r0 + rr, j0 + jj) : -a2(r0 + rr, j0 + jj);
+                        Bs[jj][rr] = !ok ? 0.0 : pass == 0 ? b1(j0 + jj, c0 + rr) : b2(j0 + jj, c0 + rr);
                     }
-                    const double d = m - rec;
-                    r2 += d * d;
-                }
-        } else if (a.side_kind == BDA_SIDE_O) {
-            for (int k = blockIdx.y; k < d_c; k += gridDim.y)
-                for (int mm = t; mm < a.d_side; mm += kPrepThreads) {
-                    double m = 0.0;
-                    for (int j = 0; j < n; ++j) m = fma(w(k, j), load_as_double<WT>(a.side, (col0 + j) * a.ld_side + mm), m);
-                    double rec;
-                    if (k >= off && k < off + n) {
-                        rec = load_as_double<CT>(a.side_out, (col0 + (k - off)) * a.ld_side_out + mm);
-                    } else {
-                        const int kk = k < off ? k : k - n;
-                        rec = 0.0;
-                        for (int i = 0; i < n; ++i) rec = fma(chat(kk, i), load_as_double<CT>(a.side_out, (col0 + i) * a.ld_side_out + mm), rec);
+                    __syncthreads();
+#pragma unroll
+                    for (int jj = 0; jj < KC; ++jj) {
+                        double av[4], bv[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) av[u] = As[ty + 16 * u][jj];
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) bv[v] = Bs[jj][tx + 16 * v];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) acc[u][v] = fma(av[u], bv[v], acc[u][v]);
                     }
-                    const double d = m - rec;
-                    r2 += d * d;
+                    __syncthreads();
                 }
-        } else {
-            for (int kk = blockIdx.y; kk < K; kk += gridDim.y)
-                for (int j = t; j < n; j += kPrepThreads) {
-                    double rec = 0.0;
-                    for (int i = 0; i < n; ++i) rec = fma(chat(kk, i), w(off + i, j), rec);
-                    const double d = w(kk < off ? kk : kk + n, j) - rec;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const double d = acc[u][v] + lone(r0 + ty + 16 * u, c0 + tx + 16 * v);
                     r2 += d * d;
                 }
         }
@@ -355,9 +400,9 @@ __global__ __launch_bounds__(kPrepThreads) void residual_kernel(const PrepArgs a
     red[t] = r2;
     __syncthreads();
     if (t == 0) {
-        double s = 0.0;
-        for (int i = 0; i < kPrepThreads; ++i) s += red[i];
-        a.partials[((size_t)a.cand * a.H + h) * a.n_parts + blockIdx.y] = s;
+        double sum = 0.0;
+        for (int i = 0; i < kPrepThreads; ++i) sum += red[i];
+        a.partials[((size_t)a.cand * a.H + h) * a.n_parts + blockIdx.y] = sum;
     }
 }
 
