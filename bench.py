@@ -424,6 +424,11 @@ def main() -> int:
         Nd = wd.N
         n_w = 96
         C_rot = Cd_one.unsqueeze(0).repeat(n_w, 1, 1).contiguous()
+        # the same copies in the packed layout of bda_pack_weights (32-column slices one after the other)
+        P_rot = torch.empty_like(C_rot)
+        for j in range(n_w):
+            bda.bda_pack_weights(C_rot[j], Nd, d_c, d_h, wd.H, wd.dtype, P_rot[j], sid)
+        torch.cuda.synchronize()
         floor = extra.get("yardsticks", {}).get("empty_launch_256x512_us")
         dec = {}
         for Td in (1, 8, 32, 64):
@@ -431,12 +436,15 @@ def main() -> int:
             od = torch.empty((Td, Nd), dtype=tdt[wd.dtype], device="cuda")
             t_d = bench_fixed(lambda i, s: bda.bda_kv_project(cd, d_c, Td, d_c, d_h, wd.H, [0, 0], C_rot[i % n_w], Nd,
                                                               od, Nd, wd.dtype, wd.dtype, s))
+            t_p = bench_fixed(lambda i, s: bda.bda_kv_project_packed(cd, d_c, Td, d_c, d_h, wd.H, [0, 0], P_rot[i % n_w],
+                                                                     od, Nd, wd.dtype, wd.dtype, s))
             by = (Td * d_c + K * Nd + Td * Nd) * 2.0
             dec[f"T{Td}"] = {"us": t_d * 1e6, "gbs": by / t_d / 1e9, "frac_hbm": by / t_d / 1e9 / HBM_PEAK_GBS,
-                             "vs_empty_launch": (t_d * 1e6 / floor) if floor else None}
-            log(f"decode T={Td}: {t_d * 1e6:.2f} us, {by / t_d / 1e9:.0f} GB/s")
+                             "vs_empty_launch": (t_d * 1e6 / floor) if floor else None,
+                             "packed_us": t_p * 1e6, "packed_gbs": by / t_p / 1e9}
+            log(f"decode T={Td}: {t_d * 1e6:.2f} us, {by / t_d / 1e9:.0f} GB/s; packed C {t_p * 1e6:.2f} us")
         extra["decode_v2lite"] = dec
-        del C_rot
+        del C_rot, P_rot
         # decode shapes at the V3 width (not a BASELINE config; 24 MiB of C per launch, 12 rotating
         # copies so that each launch streams them from HBM)
         C4_one = C_d if name == "v3" else Co_d
@@ -444,17 +452,24 @@ def main() -> int:
         N4, H4, dt4 = 256 * 128, [128, 128], wl.BF16
         n_w4 = 12
         C4_rot = C4_one.unsqueeze(0).repeat(n_w4, 1, 1).contiguous()
+        P4_rot = torch.empty_like(C4_rot)
+        for j in range(n_w4):
+            bda.bda_pack_weights(C4_rot[j], N4, d_c, d_h, H4, dt4, P4_rot[j], sid)
+        torch.cuda.synchronize()
         dec4 = {}
         for Td in (1, 8, 32, 64):
             cd = c4_src[:Td].contiguous()
             od = torch.empty((Td, N4), dtype=torch.int16, device="cuda")
             t_d = bench_fixed(lambda i, s: bda.bda_kv_project(cd, d_c, Td, d_c, d_h, H4, [0, 0], C4_rot[i % n_w4], N4,
                                                               od, N4, dt4, dt4, s))
+            t_p = bench_fixed(lambda i, s: bda.bda_kv_project_packed(cd, d_c, Td, d_c, d_h, H4, [0, 0], P4_rot[i % n_w4],
+                                                                     od, N4, dt4, dt4, s))
             by = (Td * d_c + K * N4 + Td * N4) * 2.0
-            dec4[f"T{Td}"] = {"us": t_d * 1e6, "gbs": by / t_d / 1e9, "frac_hbm": by / t_d / 1e9 / HBM_PEAK_GBS}
-            log(f"decode at V3 width T={Td}: {t_d * 1e6:.2f} us, {by / t_d / 1e9:.0f} GB/s")
+            dec4[f"T{Td}"] = {"us": t_d * 1e6, "gbs": by / t_d / 1e9, "frac_hbm": by / t_d / 1e9 / HBM_PEAK_GBS,
+                              "packed_us": t_p * 1e6, "packed_gbs": by / t_p / 1e9}
+            log(f"decode at V3 width T={Td}: {t_d * 1e6:.2f} us, {by / t_d / 1e9:.0f} GB/s; packed C {t_p * 1e6:.2f} us")
         extra["decode_v3_width"] = dec4
-        del C4_rot, co_b, oo_b, Co_d, Wo_d
+        del C4_rot, P4_rot, co_b, oo_b, Co_d, Wo_d
 
         # ---- token-count sweep on the V3 k_proj shape (N = 16384, bf16; same weights every launch, as in
         # the throughput tables of Section "BDA Inference Efficiency"): BD projection, our dense

@@ -249,6 +249,31 @@ int bda_kv_project_backward(const void* c, int64_t ldc, const void* d_out, int64
                             bda_dtype dtype, bda_dtype grad_dtype, void* stream);
 
 /*
+ * Optional packed layout of C for launches with a few tokens (Algorithm "BD Attention Inference", steps
+ * 2-3, in the decode regime, where the call is a stream over the weights).  The canonical C - heads side
+ * by side, the layout of C_qk / C_vo in the paper - stays the documented input of every other call;
+ * packing is done once, when the weights are loaded.
+ *   Layout: the N = sum_g H[g] d_h output columns are cut into slices of 32; slice s holds columns
+ *   [32 s, 32 s + 32) of all d_c - d_h rows, row after row: element (k, j) of slice s is 16-bit element
+ *   ((s (d_c - d_h) + k) * 32 + j) of the packed buffer.  A workgroup's part of C is then one contiguous
+ *   block instead of a 64-byte piece out of every row.  Every group's width H[g] d_h must be a multiple
+ *   of 32 (slices do not straddle groups); dtype BDA_F16 or BDA_BF16.
+ * bda_packed_weights_bytes: size of the packed buffer ((d_c - d_h) N 2), 0 on bad arguments.
+ * bda_pack_weights: device -> device, asynchronous on `stream`, allocates nothing; C and packed 16-byte
+ *   aligned, ldC a multiple of 8, no overlap.
+ * bda_kv_project_packed: bda_kv_project with `packed` in place of (C, ldC), for T <= 64 and shapes the
+ *   few-token kernels take (16-byte aligned buffers; ldc, ld_out, d_c - d_h and the window starts multiples
+ *   of 8; d_c - d_h <= 1536); same results as bda_kv_project bit for bit.  BDA_EINVAL otherwise (the
+ *   message says to use the canonical call).
+ */
+size_t bda_packed_weights_bytes(int d_c, int d_h, int G, const int* H, bda_dtype dtype);
+int bda_pack_weights(const void* C, int64_t ldC, int d_c, int d_h, int G, const int* H, bda_dtype dtype,
+                     void* packed, void* stream);
+int bda_kv_project_packed(const void* c, int64_t ldc, int64_t T, int d_c, int d_h,
+                          int G, const int* H, const int* basis_offset, const void* packed,
+                          void* out, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype, void* stream);
+
+/*
  * The same three device calls with an explicit tile policy for this one call (tests, tuning and
  * benchmarks of the individual kernels; the plain entry points are these with policy 0).  Nothing
  * about the policy outlives the call and other threads' calls are unaffected.

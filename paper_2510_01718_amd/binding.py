@@ -19,7 +19,8 @@ BASIS_FIRST, BASIS_LAST, BASIS_RESIDUAL_MIN, BASIS_OFFSET_SEARCH, BASIS_EXPLICIT
 SIDE_NONE, SIDE_Q, SIDE_O = 0, 1, 2
 
 EXPORTS = ("bda_prepare", "bda_prepare_lowrank", "bda_prepare_device", "bda_prepare_device_ex",
-           "bda_prepare_device_workspace_bytes", "bda_prepare_device_static", "bda_kv_project", "bda_dense_project",
+           "bda_prepare_device_workspace_bytes", "bda_prepare_device_static", "bda_packed_weights_bytes",
+           "bda_pack_weights", "bda_kv_project_packed", "bda_kv_project", "bda_dense_project",
            "bda_lowrank_linear", "bda_kv_project_backward", "bda_kv_project_ex", "bda_dense_project_ex",
            "bda_kv_project_backward_ex", "bda_kv_project_plan", "bda_dense_project_plan", "bda_last_error", "bda_version")
 
@@ -79,6 +80,12 @@ def load():
     lib.bda_prepare_device_static.restype = c_int
     lib.bda_prepare_device_static.argtypes = [vp, i64, c_int, c_int, c_int, c_int, vp, i64, c_int, c_int, c_int, c_int,
                                               vp, i64, vp, i64, c_int, vp, vp, vp, vp]
+    lib.bda_packed_weights_bytes.restype = ctypes.c_size_t
+    lib.bda_packed_weights_bytes.argtypes = [c_int, c_int, c_int, ip, c_int]
+    lib.bda_pack_weights.restype = c_int
+    lib.bda_pack_weights.argtypes = [vp, i64, c_int, c_int, c_int, ip, c_int, vp, vp]
+    lib.bda_kv_project_packed.restype = c_int
+    lib.bda_kv_project_packed.argtypes = [vp, i64, i64, c_int, c_int, c_int, ip, ip, vp, vp, i64, c_int, c_int, vp]
     lib.bda_kv_project.restype = c_int
     lib.bda_kv_project.argtypes = [vp, i64, i64, c_int, c_int, c_int, ip, ip, vp, i64, vp, i64,
                                    c_int, c_int, vp]
@@ -199,6 +206,26 @@ def bda_kv_project(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],
     _check(lib.bda_kv_project(_ptr(c), ldc, T, d_c, d_h, G, _int_array(H), _int_array(basis_offset),
                               _ptr(C), ldC, _ptr(out), ld_out, dtype,
                               dtype if out_dtype is None else out_dtype, stream or None))
+
+
+def bda_packed_weights_bytes(d_c: int, d_h: int, H: Sequence[int], dtype: int) -> int:
+    return int(load().bda_packed_weights_bytes(d_c, d_h, len(H), _int_array(H), dtype))
+
+
+def bda_pack_weights(C, ldC: int, d_c: int, d_h: int, H: Sequence[int], dtype: int, packed, stream: int = 0) -> None:
+    _check(load().bda_pack_weights(_ptr(C), ldC, d_c, d_h, len(H), _int_array(H), dtype, _ptr(packed), stream or None))
+
+
+def bda_kv_project_packed(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],
+                          basis_offset: Sequence[int], packed, out, ld_out: int, dtype: int,
+                          out_dtype: Optional[int] = None, stream: int = 0) -> None:
+    lib = load()
+    G = len(H)
+    if len(basis_offset) != G:
+        raise ValueError("H and basis_offset must have one entry per group")
+    _check(lib.bda_kv_project_packed(_ptr(c), ldc, T, d_c, d_h, G, _int_array(H), _int_array(basis_offset),
+                                     _ptr(packed), _ptr(out), ld_out, dtype,
+                                     dtype if out_dtype is None else out_dtype, stream or None))
 
 
 def bda_kv_project_ex(c, ldc: int, T: int, d_c: int, d_h: int, H: Sequence[int],

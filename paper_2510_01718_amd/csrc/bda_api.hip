@@ -315,6 +315,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     bool fast = (dtype == BDA_F16 || dtype == BDA_BF16) && a.K > 0;
     const size_t out_sz = dtype_size(out_dtype);
     fast = fast && aligned(a.A, 16) && aligned(a.B, 16) && aligned(a.D, out_sz == 4 ? 16 : 8);
+    const bool packed = a.ldb == 0;                          // C in the layout of bda_pack_weights: small-T kernels only
     fast = fast && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldd % 8 == 0 && a.K % 8 == 0 && a.a_skip % 8 == 0;
     const bool ident_tiles = !a.ident || a.d_h % 32 == 0;   // one 32-column MFMA tile never straddles two heads
     const bool ident_vec = !a.ident || a.d_h % 8 == 0;
@@ -353,7 +354,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     const int64_t tok_tiles = (a.M + kDecodeMaxT - 1) / kDecodeMaxT;
     const bool fits32 = n_slices32 * tok_tiles <= 256, fits64 = n_slices64 * tok_tiles <= 256;
     const bool wide_auto = a.M <= 64 ? n_slices128 >= 160 : (!fits32 && fits64);
-    const bool small_T = a.M <= 64 || (a.M <= kDecodeMaxT * 8 && (fits32 || fits64 || (policy0 == 5 && a.M <= kDecodeMaxT)));
+    const bool small_T = a.M <= 64 || (!packed && a.M <= kDecodeMaxT * 8 && (fits32 || fits64 || (policy0 == 5 && a.M <= kDecodeMaxT)));
     if (fast && ident_vec && small_T && a.K <= 16 * kDecodeWideMaxKS && (policy0 == 5 || (policy0 == 0 && wide_auto))) {
         // a few tokens, wide output: stream the weights once, 128 (64) output columns per workgroup
         build_tiles(a, G, group_cols, a.M <= 64 ? 64 : kDecodeMaxT, a.M <= 64 ? 128 : 64);
@@ -363,7 +364,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_decode_wide<BF16, uint16_t>(a, st);
         if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_decode_wide<BF16, float>(a, st);
     }
-    if (fast && ident_vec && small_policy && a.K <= kDecodeMaxK && (a.M <= 64 || (a.M <= kDecodeMaxT * 8 && fits32))) {
+    if (fast && ident_vec && small_policy && a.K <= kDecodeMaxK && (a.M <= 64 || (!packed && a.M <= kDecodeMaxT * 8 && fits32))) {
         // a few tokens: stream the weights once, 32 output columns per workgroup
         build_tiles(a, G, group_cols, a.M <= 64 ? 64 : kDecodeMaxT, 32);
         a.sm = a.sn = 1;
@@ -372,6 +373,9 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_decode<BF16, uint16_t>(a, st);
         if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_decode<BF16, float>(a, st);
     }
+    if (packed)
+        return fail(BDA_EINVAL, "bda_kv_project_packed: packed weights serve the few-token kernels only (up to 64 tokens, 16-bit types, "
+                                "16-byte aligned buffers, pitches and d_c - d_h multiples of 8, d_c - d_h <= %d); use bda_kv_project with the canonical C", kDecodeMaxK);
     if (fast && ident_tiles) {
         const int64_t mt256 = (a.M + 255) / 256, mt128 = (a.M + 127) / 128;
         int64_t nt256 = 0;
@@ -498,6 +502,94 @@ extern "C" int bda_kv_project(const void* c, int64_t ldc, int64_t T, int d_c, in
     GemmArgs a{};
     a.A = c; a.B = C; a.D = out;
     a.lda = ldc; a.ldb = ldC; a.ldd = ld_out;
+    a.M = T; a.K = K; a.d_h = d_h; a.a_skip = d_h; a.ident = 1;
+    for (int g = 0; g < G; ++g) a.a_off[g] = basis_offset[g];
+    return run_gemm(a, G, cols, dtype, out_dtype, (hipStream_t)stream);
+}
+
+namespace bda {
+namespace {
+
+// One 16-byte piece (8 columns of one row) per thread: C[k][n .. n + 7] -> slice n / 32, row k, columns n % 32.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const u32x4* __restrict__ C, int64_t ldC8, int K, int64_t N8, u32x4* __restrict__ packed)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)K * N8) return;
+    const int64_t k = i / N8, p8 = i % N8;
+    packed[((p8 >> 2) * K + k) * 4 + (p8 & 3)] = C[k * ldC8 + p8];
+}
+
+int packed_shape(const char* fn, int d_c, int d_h, int G, const int* H, int dtype, int64_t& N)
+{
+    if (dtype != BDA_F16 && dtype != BDA_BF16) return fail(BDA_EDTYPE, "%s: packed weights are 16-bit (got dtype %d)", fn, dtype);
+    if (d_c <= 0 || d_h <= 0 || d_h >= d_c) return fail(BDA_EINVAL, "%s: need 0 < d_h < d_c", fn);
+    if (G <= 0 || G > BDA_MAX_GROUPS || !H) return fail(BDA_EINVAL, "%s: need 1 <= G <= %d and non-NULL H", fn, BDA_MAX_GROUPS);
+    N = 0;
+    for (int g = 0; g < G; ++g) {
+        if (H[g] <= 0) return fail(BDA_EINVAL, "%s: H[%d]=%d", fn, g, H[g]);
+        if (((int64_t)H[g] * d_h) % 32) return fail(BDA_EINVAL, "%s: every group's width H[g] d_h must be a multiple of 32 (group %d: %lld)", fn, g, (long long)H[g] * d_h);
+        N += (int64_t)H[g] * d_h;
+    }
+    return BDA_OK;
+}
+
+}  // namespace
+}  // namespace bda
+
+extern "C" size_t bda_packed_weights_bytes(int d_c, int d_h, int G, const int* H, bda_dtype dtype)
+{
+    clear_error();
+    int64_t N = 0;
+    if (packed_shape("bda_packed_weights_bytes", d_c, d_h, G, H, (int)dtype, N)) return 0;
+    return (size_t)(d_c - d_h) * (size_t)N * 2;
+}
+
+extern "C" int bda_pack_weights(const void* C, int64_t ldC, int d_c, int d_h, int G, const int* H, bda_dtype dtype,
+                                void* packed, void* stream)
+{
+    clear_error();
+    int64_t N = 0;
+    if (int rc = packed_shape("bda_pack_weights", d_c, d_h, G, H, (int)dtype, N)) return rc;
+    if (!C || !packed) return fail(BDA_EINVAL, "bda_pack_weights: NULL device pointer");
+    if (ldC < N || ldC % 8 || !aligned(C, 16) || !aligned(packed, 16)) return fail(BDA_EINVAL, "bda_pack_weights: need ldC >= N, ldC a multiple of 8 and 16-byte aligned buffers");
+    const int K = d_c - d_h;
+    if (overlaps(span_of(packed, 1, (int64_t)K * N, (int64_t)K * N, 2), span_of(C, K, N, ldC, 2))) return fail(BDA_EINVAL, "bda_pack_weights: packed overlaps C");
+    const int64_t pieces = (int64_t)K * (N / 8);
+    if (pieces > ((int64_t)1 << 31) * 256) return fail(BDA_EINVAL, "bda_pack_weights: too large");
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const u32x4*)C, ldC / 8, K, N / 8, (u32x4*)packed);
+    hipError_t err = hipGetLastError();
+    return err == hipSuccess ? BDA_OK : fail(BDA_EHIP, "bda_pack_weights: kernel launch: %s", hipGetErrorString(err));
+}
+
+extern "C" int bda_kv_project_packed(const void* c, int64_t ldc, int64_t T, int d_c, int d_h, int G,
+                                     const int* H, const int* basis_offset, const void* packed,
+                                     void* out, int64_t ld_out, bda_dtype dtype, bda_dtype out_dtype, void* stream)
+{
+    clear_error();
+    const char* fn = "bda_kv_project_packed";
+    if (int rc = check_dtypes(fn, dtype, out_dtype)) return rc;
+    int64_t N = 0;
+    if (int rc = packed_shape(fn, d_c, d_h, G, H, (int)dtype, N)) return rc;
+    if (T < 0 || !basis_offset) return fail(BDA_EINVAL, "%s: need T >= 0 and non-NULL basis_offset", fn);
+    int64_t cols[BDA_MAX_GROUPS];
+    for (int g = 0; g < G; ++g) {
+        if (basis_offset[g] < 0 || basis_offset[g] > d_c - d_h) return fail(BDA_EINVAL, "%s: basis_offset[%d]=%d outside [0, %d]", fn, g, basis_offset[g], d_c - d_h);
+        cols[g] = (int64_t)H[g] * d_h;
+    }
+    if (T == 0) return BDA_OK;
+    if (T > 64) return fail(BDA_EINVAL, "%s: packed weights serve up to 64 tokens (T=%lld); use bda_kv_project with the canonical C", fn, (long long)T);
+    if (!c || !packed || !out) return fail(BDA_EINVAL, "%s: NULL device pointer", fn);
+    if (ldc < d_c || ld_out < N) return fail(BDA_EINVAL, "%s: leading dimension too small", fn);
+    if (!aligned(packed, 16)) return fail(BDA_EINVAL, "%s: packed not 16-byte aligned", fn);
+    const int K = d_c - d_h;
+    const size_t esz = dtype_size(dtype), osz = dtype_size(out_dtype);
+    Span so = span_of(out, T, N, ld_out, osz);
+    if (overlaps(so, span_of(c, T, d_c, ldc, esz)) || overlaps(so, span_of(packed, 1, (int64_t)K * N, (int64_t)K * N, esz)))
+        return fail(BDA_EINVAL, "%s: out overlaps an input", fn);
+    GemmArgs a{};
+    a.A = c; a.B = packed; a.D = out;
+    a.lda = ldc; a.ldb = 0; a.ldd = ld_out;              // ldb = 0: C in the packed layout
     a.M = T; a.K = K; a.d_h = d_h; a.a_skip = d_h; a.ident = 1;
     for (int g = 0; g < G; ++g) a.a_off[g] = basis_offset[g];
     return run_gemm(a, G, cols, dtype, out_dtype, (hipStream_t)stream);

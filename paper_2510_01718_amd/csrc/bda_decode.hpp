@@ -16,6 +16,9 @@
 //     latent is k-contiguous) or, for 33 .. 64 tokens, through LDS; the identity slice is added in
 //     float32 after the reduction.
 // A second kernel at the end of this file gives a workgroup 128 columns, for wide outputs.
+// Both also read C in the packed layout of bda_pack_weights (GemmArgs.ldb == 0): 32-column slices
+// stored one after the other, each as K rows of 64 bytes, so that a workgroup's slice is one
+// contiguous block instead of a 64-byte piece out of every row of C.
 #pragma once
 #include <type_traits>
 
@@ -133,9 +136,11 @@ __global__ __launch_bounds__(256) void kv_decode_kernel(const GemmArgs p_in)
 
     // ---- the slice of C: K rows x 64 bytes, 16 rows per DMA instruction (first of all: everything
     // else the kernel does before its MFMAs hides behind this request) --------------------------------
-    const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
+    const bool packed = p.ldb == 0;                      // (slices of a packed C are whole: widths are multiples of 32)
+    const u32x4 rB = packed ? make_rsrc_words((const char*)p.B + n0 * p.K * 2, (int64_t)p.K * 64)
+                            : make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
     {
-        const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
+        const uint32_t row_bytes = packed ? 64u : (uint32_t)(p.ldb * 2);
         const int piece = lane & 3;
         const uint32_t lane_off = piece * 8 < cols_left ? (uint32_t)(lane >> 2) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
         const int n_instr = nks;                          // 16 rows each
@@ -366,22 +371,29 @@ __global__ __launch_bounds__(256) void kv_decode_wide_kernel(const GemmArgs p_in
     // ---- the slice of C: request j of wave w brings rows 4 RPI j + RPI w .. + RPI - 1 to LDS offset
     // 4096 j + 1024 w; the first chunk's requests go out before anything else, the rest behind the
     // token rows ---------------------------------------------------------------------------------------
-    const u32x4 rB = make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
-    const uint32_t row_bytes = (uint32_t)(p.ldb * 2);
+    // (packed C: the slice is CW / 32 sub-slices of K rows x 64 bytes one after the other; piece q of row k
+    // lies in sub-slice q / 4 at byte 64 k + 16 (q % 4))
+    const bool packed = p.ldb == 0;
+    const u32x4 rB = packed ? make_rsrc_words((const char*)p.B + n0 * p.K * 2, (int64_t)(CW / 32) * p.K * 64)
+                            : make_rsrc_words((const char*)p.B + n0 * 2, ((int64_t)(p.K - 1) * p.ldb + cols_left) * 2);
+    const uint32_t row_bytes = packed ? 64u : (uint32_t)(p.ldb * 2);
     uint32_t c_lane_off;
     {
         constexpr int PPR = ROW_B / 16;                               // pieces per row: 16 or 8
         const int r = lane / PPR;                                     // row within the request
         const int swz = CW == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1);
         const int piece = (lane % PPR) ^ swz;                         // global piece held at LDS position lane % PPR
-        c_lane_off = piece * 8 < cols_left ? (uint32_t)(RPI * wave + r) * row_bytes + (uint32_t)piece * 16u : kBadOffset;
+        const uint32_t in_row = packed ? (uint32_t)(piece >> 2) * (uint32_t)p.K * 64u + (uint32_t)(piece & 3) * 16u : (uint32_t)piece * 16u;
+        c_lane_off = piece * 8 < cols_left ? (uint32_t)(RPI * wave + r) * row_bytes + in_row : kBadOffset;
     }
+    const int c_row0 = RPI * wave + lane / (ROW_B / 16);              // this lane's row in request 0
     const uint32_t c_lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)wave * 1024u;
     auto request_c = [&](auto first, auto last) {                     // requests [first, last) of this wave
 #pragma unroll
         for (int j = decltype(first)::value; j < decltype(last)::value; ++j)   // rows past K fall outside rB's range -> zeros
-            if (j < issued)
-                lds_dma1(rB, c_lds0 + (uint32_t)j * 4096u, c_lane_off + (uint32_t)(j * 4 * RPI) * row_bytes);
+            if (j < issued)                                           // (packed: a row past K would be the next sub-slice's)
+                lds_dma1(rB, c_lds0 + (uint32_t)j * 4096u,
+                         (!packed || c_row0 + j * 4 * RPI < p.K) ? c_lane_off + (uint32_t)(j * 4 * RPI) * row_bytes : kBadOffset);
     };
     request_c(std::integral_constant<int, 0>{}, std::integral_constant<int, RPC>{});
 

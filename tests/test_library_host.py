@@ -206,6 +206,23 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert bwd(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None) == 0
     assert lib.bda_dense_project(fake, 64, 4, 64, fake, 8, 32, fake, 32, 1, 1, None) == -1
     assert lib.bda_lowrank_linear(fake, 64, 4, 64, 8, 40, 3, fake, fake, fake, 40, 1, None) == -1
+    # packed weights: 16-bit only, group widths multiples of 32, at most 64 tokens, shapes the few-token kernels take
+    H32, H3 = (ctypes.c_int * 1)(2), (ctypes.c_int * 2)(1, 3)
+    assert lib.bda_packed_weights_bytes(96, 32, 1, H32, 1) == 64 * 64 * 2
+    assert lib.bda_packed_weights_bytes(96, 32, 1, H32, 0) == 0 and b"16-bit" in lib.bda_last_error()
+    assert lib.bda_packed_weights_bytes(64, 16, 2, H3, 1) == 0 and b"multiple of 32" in lib.bda_last_error()
+    assert lib.bda_packed_weights_bytes(64, 16, 1, H32, 2) == 48 * 32 * 2
+    assert lib.bda_pack_weights(fake, 60, 96, 32, 1, H32, 1, far, None) == -1            # ldC < N
+    assert lib.bda_pack_weights(fake, 64, 96, 32, 1, H32, 1, ctypes.c_void_p(0x1008), None) == -1
+    assert lib.bda_pack_weights(fake, 64, 96, 32, 1, H32, 1, ctypes.c_void_p(0x1100), None) == -1 and b"overlaps" in lib.bda_last_error()
+    assert lib.bda_pack_weights(fake, 64, 96, 32, 1, H32, 3, far, None) == -3
+    pk = lib.bda_kv_project_packed
+    assert pk(fake, 96, 65, 96, 32, 1, H32, off, far, farther, 64, 1, 1, None) == -1 and b"64 tokens" in lib.bda_last_error()
+    assert pk(fake, 96, 4, 96, 32, 1, H32, (ctypes.c_int * 1)(65), far, farther, 64, 1, 1, None) == -1 and b"basis_offset" in lib.bda_last_error()
+    assert pk(fake, 96, 4, 96, 32, 1, H32, off, far, farther, 64, 0, 0, None) == -3
+    assert pk(fake, 96, 4, 96, 32, 1, H32, off, far, fake, 64, 1, 1, None) == -1 and b"overlaps" in lib.bda_last_error()
+    assert pk(fake, 100, 4, 96, 32, 1, H32, off, far, farther, 64, 1, 1, None) == -1 and b"canonical" in lib.bda_last_error()
+    assert pk(None, 96, 0, 96, 32, 1, H32, off, None, None, 64, 1, 1, None) == 0
     # a tile policy outside 0 .. 6 is refused before anything else is looked at
     assert lib.bda_kv_project_ex(fake, 64, 4, 64, 16, 1, H, off, fake, 32, far, 32, 1, 1, None, 7) == -1
     assert b"tile_policy" in lib.bda_last_error()
