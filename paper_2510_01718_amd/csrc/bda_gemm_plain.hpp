@@ -295,16 +295,17 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll
         for (int ti = 0; ti < TT; ++ti) ft[ti] = *(lds_u32x4)(uintptr_t)(a + ti * (32 * RB));
     };
-    int rel_blk[TN] = {};
-    auto mma_identity = [&](const u32x4 (&idf)[2], int col0, const u32x4 (&ft)[TT]) {
+    // k-step s (16 window columns from jc + 16 s) of an identity stage.  The stage's 64 window columns start
+    // at a multiple of 64 (jc), and so do the wave's 64 output columns within their head (rel_blk0; the head
+    // width is a multiple of 64).  So either the stage holds the wave's slice (`hit`: jc == rel_blk0), and then
+    // k-steps 0, 1 meet the wave's first 32-column block and k-steps 2, 3 its second, with the lower or upper
+    // 16 columns of the block in turn (which identity fragment) - or it holds none of it.
+    static_assert(TN == 2, "identity k-steps are laid out for waves of two 32-column blocks");
+    auto mma_identity = [&](auto sc, bool hit, const u32x4 (&idf)[2], const u32x4 (&ft)[TT]) {
+        constexpr int s = decltype(sc)::value;
+        if (hit) {
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni) {
-            const int d = col0 - rel_blk[ni];
-            if (d == 0 || d == 16) {
-                const u32x4 f = d == 0 ? idf[0] : idf[1];
-#pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(f, ft[ti], acc[ni][ti]);
-            }
+            for (int ti = 0; ti < TT; ++ti) acc[s >> 1][ti] = mm(idf[s & 1], ft[ti], acc[s >> 1][ti]);
         }
     };
     auto clear_acc = [&]() {
@@ -318,6 +319,8 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     // into the same slot once every wave has read it.  The eight MFMAs of each of the last two k-steps
     // carry four loads between them.
     uint32_t slot_b = 0;
+    u32x4 idf_keep[2];
+    make_idf(idf_keep);
     auto stage = [&](auto regular, auto first_of_tile, const StreamTile& cur, int kc, const StreamTile& pt, int pk, bool relaxed) {
         constexpr bool REG = decltype(regular)::value;
         constexpr bool FIRST = decltype(first_of_tile)::value;   // only then may result stores be in flight
@@ -326,8 +329,13 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         const uint32_t off_cur = half_cur ? (uint32_t)TOK_BYTES : 0u;
         const uint32_t off_next = (!next_regular && id_half(cur, kc + 1)) ? (uint32_t)TOK_BYTES : 0u;
         const int jc = cur.j_lo + (kc - nk) * (2 * SK) + half_cur * SK;
+        const bool id_hit = !REG && jc == cur.rel_blk0;
+#ifndef BDA_IDF_PER_STAGE
+        const u32x4 (&idf)[2] = idf_keep;
+#else
         u32x4 idf[2];
         if constexpr (!REG) make_idf(idf);
+#endif
         // The two waves of a SIMD run the same code and the older one wins every arbitration, so it
         // runs ahead to the barrier and leaves the other to work through the stage alone.  Alternating
         // the priority by half stages keeps them side by side (measured: 4-8 % faster).
@@ -338,14 +346,14 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
                 for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw0[ni], ft0[ti], acc[ni][ti]);
-        } else mma_identity(idf, jc, ft0);
+        } else mma_identity(std::integral_constant<int, 0>{}, id_hit, idf, ft0);
         if constexpr (REG) { read_w(2, fw0); read_t(2, ft0); } else read_t(2, ft0, off_cur);
         if constexpr (REG) {
 #pragma unroll
             for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
                 for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw1[ni], ft1[ti], acc[ni][ti]);
-        } else mma_identity(idf, jc + 16, ft1);
+        } else mma_identity(std::integral_constant<int, 1>{}, id_hit, idf, ft1);
         // last read of this slot
         if constexpr (REG) { read_w(3, fw1); read_t(3, ft1); } else read_t(3, ft1, off_cur);
         flip_slot();
@@ -373,7 +381,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]); acc[1][1] = mm(fw0[1], ft0[1], acc[1][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
         } else {
-            mma_identity(idf, jc + 32, ft0);
+            mma_identity(std::integral_constant<int, 2>{}, id_hit, idf, ft0);
             tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt);
             tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt);
             tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt);
@@ -401,7 +409,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             acc[1][1] = mm(fw1[1], ft1[1], acc[1][1]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
         } else {
-            mma_identity(idf, jc + 48, ft1);
+            mma_identity(std::integral_constant<int, 3>{}, id_hit, idf, ft1);
             wgt_load(std::integral_constant<int, 0>{}, z);
             wgt_load(std::integral_constant<int, 1>{}, z);
             wgt_load(std::integral_constant<int, 2>{}, z);
@@ -430,11 +438,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll 1
     for (int round = 0; round < n_rounds; ++round) {
         const StreamTile nxt = setup();
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni) {      // d_h >= 64 is a multiple of 64 and rel_blk0 < d_h
-            rel_blk[ni] = cur.rel_blk0 + 32 * ni;
-            if (rel_blk[ni] >= q.d_h) rel_blk[ni] -= q.d_h;
-        }
         const bool after_tile = round > 0;
         // stage 0 of the tile apart (host contract: S >= 3, so it requests stage 2 of the same tile)
         stage(REGULAR, std::true_type{}, cur, 0, cur, 2, after_tile);
