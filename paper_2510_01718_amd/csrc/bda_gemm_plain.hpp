@@ -330,16 +330,43 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         const uint32_t off_next = (!next_regular && id_half(cur, kc + 1)) ? (uint32_t)TOK_BYTES : 0u;
         const int jc = cur.j_lo + (kc - nk) * (2 * SK) + half_cur * SK;
         const bool id_hit = !REG && jc == cur.rel_blk0;
-#ifndef BDA_IDF_PER_STAGE
         const u32x4 (&idf)[2] = idf_keep;
-#else
-        u32x4 idf[2];
-        if constexpr (!REG) make_idf(idf);
-#endif
         // The two waves of a SIMD run the same code and the older one wins every arbitration, so it
         // runs ahead to the barrier and leaves the other to work through the stage alone.  Alternating
         // the priority by half stages keeps them side by side (measured: 4-8 % faster).
         if (wt == 0) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+        if constexpr (!REG) {
+            // An identity stage has half the MFMAs of a regular one and moves as many bytes, so it does
+            // not split into halves: all its token fragments are asked for at once (this frees the slot),
+            // the barrier follows, and the eight requests for the next tile go between all sixteen MFMAs.
+            u32x4 ft2[TT], ft3[TT];
+            read_t(1, ft1, off_cur); read_t(2, ft2, off_cur); read_t(3, ft3, off_cur);
+            flip_slot();
+            const uint32_t lds_b = slot_b + wave_lds;
+            const uint32_t ts = stage_soff_tok(pt, pk);
+            uint32_t vt[PIT];
+            tok_voffs(pt, pk, vt);
+            const Second z = second_set(pt, pk, lds_b, ts, vt);
+            wait_vmcnt<0>();
+            __syncthreads();
+            if (wt == 0) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
+            mma_identity(std::integral_constant<int, 0>{}, id_hit, idf, ft0);
+            tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt);
+            tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt);
+            if (next_regular) read_w(0, fw0);
+            read_t(0, ft0, off_next);
+            mma_identity(std::integral_constant<int, 1>{}, id_hit, idf, ft1);
+            tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt);
+            tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt);
+            mma_identity(std::integral_constant<int, 2>{}, id_hit, idf, ft2);
+            wgt_load(std::integral_constant<int, 0>{}, z);
+            wgt_load(std::integral_constant<int, 1>{}, z);
+            mma_identity(std::integral_constant<int, 3>{}, id_hit, idf, ft3);
+            wgt_load(std::integral_constant<int, 2>{}, z);
+            wgt_load(std::integral_constant<int, 3>{}, z);
+            slot_b = (uint32_t)STAGE_BYTES - slot_b;
+            return;
+        }
         if constexpr (REG) { read_w(1, fw1); read_t(1, ft1); } else read_t(1, ft1, off_cur);
         if constexpr (REG) {
 #pragma unroll
