@@ -308,16 +308,10 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             for (int ti = 0; ti < TT; ++ti) acc[s >> 1][ti] = mm(idf[s & 1], ft[ti], acc[s >> 1][ti]);
         }
     };
-    auto clear_acc = [&]() {
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-            for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = zero16;
-    };
 
     // One stage of tile `cur` out of the slot at `slot_b`, during which stage pk of tile pt is requested
-    // into the same slot once every wave has read it.  The eight MFMAs of each of the last two k-steps
-    // carry four loads between them.
+    // into the same slot once every wave has read it.  In a regular stage the eight MFMAs of each of the
+    // last two k-steps carry four loads between them.
     uint32_t slot_b = 0;
     u32x4 idf_keep[2];
     make_idf(idf_keep);
@@ -367,22 +361,21 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             slot_b = (uint32_t)STAGE_BYTES - slot_b;
             return;
         }
-        if constexpr (REG) { read_w(1, fw1); read_t(1, ft1); } else read_t(1, ft1, off_cur);
-        if constexpr (REG) {
+        // ---- a regular stage ----
+        read_w(1, fw1); read_t(1, ft1);
+        // the first k-step of a tile starts the sums: its MFMAs take zero as their addend, so the
+        // accumulators are never cleared
 #pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
+        for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw0[ni], ft0[ti], acc[ni][ti]);
-        } else mma_identity(std::integral_constant<int, 0>{}, id_hit, idf, ft0);
-        if constexpr (REG) { read_w(2, fw0); read_t(2, ft0); } else read_t(2, ft0, off_cur);
-        if constexpr (REG) {
+            for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw0[ni], ft0[ti], FIRST ? zero16 : acc[ni][ti]);
+        read_w(2, fw0); read_t(2, ft0);
 #pragma unroll
-            for (int ni = 0; ni < TN; ++ni)
+        for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-                for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw1[ni], ft1[ti], acc[ni][ti]);
-        } else mma_identity(std::integral_constant<int, 1>{}, id_hit, idf, ft1);
+            for (int ti = 0; ti < TT; ++ti) acc[ni][ti] = mm(fw1[ni], ft1[ti], acc[ni][ti]);
         // last read of this slot
-        if constexpr (REG) { read_w(3, fw1); read_t(3, ft1); } else read_t(3, ft1, off_cur);
+        read_w(3, fw1); read_t(3, ft1);
         flip_slot();
         // uniform part of the requests that follow the barrier
         const uint32_t lds_b = slot_b + wave_lds;
@@ -393,7 +386,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
         if (FIRST && relaxed) wait_vmcnt<STORES>(); else wait_vmcnt<0>();
         __syncthreads();
         if (wt == 0) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
-        if constexpr (REG && TT == 4) {
+        if constexpr (TT == 4) {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[0][2] = mm(fw0[0], ft0[2], acc[0][2]); acc[0][3] = mm(fw0[0], ft0[3], acc[0][3]);
@@ -402,22 +395,16 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw0[1], ft0[2], acc[1][2]); acc[1][3] = mm(fw0[1], ft0[3], acc[1][3]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
-        } else if constexpr (REG) {
+        } else {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]); acc[1][1] = mm(fw0[1], ft0[1], acc[1][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
-        } else {
-            mma_identity(std::integral_constant<int, 2>{}, id_hit, idf, ft0);
-            tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt);
-            tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt);
-            tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt);
-            tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt);
         }
         // first fragments of the next stage, out of the other slot
         if (next_regular) read_w(0, fw0);
         read_t(0, ft0, off_next);
-        if constexpr (REG && TT == 4) {
+        if constexpr (TT == 4) {
             acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]); acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[0][2] = mm(fw1[0], ft1[2], acc[0][2]); acc[0][3] = mm(fw1[0], ft1[3], acc[0][3]);
@@ -426,7 +413,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw1[1], ft1[2], acc[1][2]); acc[1][3] = mm(fw1[1], ft1[3], acc[1][3]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
-        } else if constexpr (REG) {
+        } else {
             acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
@@ -435,12 +422,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][1] = mm(fw1[1], ft1[1], acc[1][1]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
-        } else {
-            mma_identity(std::integral_constant<int, 3>{}, id_hit, idf, ft1);
-            wgt_load(std::integral_constant<int, 0>{}, z);
-            wgt_load(std::integral_constant<int, 1>{}, z);
-            wgt_load(std::integral_constant<int, 2>{}, z);
-            wgt_load(std::integral_constant<int, 3>{}, z);
         }
         slot_b = (uint32_t)STAGE_BYTES - slot_b;
     };
@@ -451,7 +432,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     produce_all(cur, 0, 0u);
     __builtin_amdgcn_s_barrier();
     produce_all(cur, 1, (uint32_t)STAGE_BYTES);
-    clear_acc();
     wait_vmcnt<PIT + PIW>();
     __syncthreads();
     read_w(0, fw0);
@@ -554,7 +534,6 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
                 }
             }
         }
-        clear_acc();
         cur = nxt;
     }
     wait_vmcnt<0>();
