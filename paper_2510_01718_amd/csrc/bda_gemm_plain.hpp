@@ -444,10 +444,12 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     const int i_same = split > nk ? split : nk;
 #pragma unroll 1
     for (int round = 0; round < n_rounds; ++round) {
-        const StreamTile nxt = setup();
         const bool after_tile = round > 0;
         // stage 0 of the tile apart (host contract: S >= 3, so it requests stage 2 of the same tile)
         stage(REGULAR, std::true_type{}, cur, 0, cur, 2, after_tile);
+        // (the next tile is not needed before stage S - 2; its scalar set-up sits here, where the MFMA
+        // pipe has work queued, rather than at the top of the round, where it has none)
+        const StreamTile nxt = setup();
         int kc = 1;
 #pragma unroll 1
         for (; kc < r_same; ++kc) stage(REGULAR, std::false_type{}, cur, kc, cur, kc + 2, false);
