@@ -514,6 +514,7 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
     };
 
     StreamTile cur = setup();
+    bool prev_full = true;                    // did the previous tile issue all its result stores?
     int g = 0;
     // prologue: the first kStages stages of the first tile
 #pragma unroll 1
@@ -541,7 +542,10 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
             if (rel_blk[ni] >= q.d_h) rel_blk[ni] -= q.d_h;
             if (rel_blk[ni] >= q.d_h) rel_blk[ni] -= q.d_h;
         }
-        const bool after_tile = round > 0;
+        // The relaxed wait counts on all STORES result stores of the previous tile being in flight
+        // behind the loads it waits for; a tile that a group's end cut short skipped some, so after
+        // such a tile (and after a tile outside the grid, which stores nothing) the wait is the full one.
+        const bool after_tile = round > 0 && prev_full;
         int kc = 0;
 #pragma unroll 1
         for (; kc < r_same; ++kc, ++g) stage(REGULAR, cur, kc, g, cur, kc + kStages, after_tile && kc < (kAhead > 1 ? kAhead : 1));
@@ -557,27 +561,42 @@ __global__ __launch_bounds__(64 * WT * WN) void gemm_stream_kernel(const GemmArg
         const __amdgpu_buffer_rsrc_t rD = make_rsrc(
             (char*)q.D + cur.d_off * (int64_t)sizeof(OutT),
             cur.cols_left > 0 ? ((cur.rows_left - 1) * q.ldd + cur.cols_left) * (int64_t)sizeof(OutT) : 0);
-        const uint32_t ep_row_step = 32u * (uint32_t)(q.ldd * sizeof(OutT));
         const bool full = cur.cols_left == BN;      // uniform; a group may end inside its last tile
+        prev_full = full;
         if constexpr (sizeof(OutT) == 4) {
+            // float32 results: a lane holds runs of 4 consecutive columns (16 bytes) of one row, lanes l and
+            // l+32 adjacent runs.  Stored as they are, an instruction would write 32 bytes of each of 32
+            // rows, which the memory pipeline takes at a third of its rate; so a 32-row x 32-column block
+            // (4 KiB) is turned round in the wave's staging region, as below for the 16-bit types, and 8
+            // consecutive lanes store one full 128-byte line of a row.
+            unsigned char* stag = smem + kStages * STAGE_BYTES + wave * 4096;
             int eln = lane;
             asm volatile("" : "+v"(eln));
-            uint32_t ep_row = (uint32_t)(wt * (32 * TT) + (eln & 31)) * (uint32_t)(q.ldd * 4) + (uint32_t)(wn * (32 * TN) + (eln >> 5) * 4) * 4u;
+            const int e31 = eln & 31;
+            const int st_wr = e31 * 128;
+            const int st_sw = (e31 ^ (e31 >> 3)) & 7;
+            const int rd_row = eln >> 3, rd_chunk = eln & 7;
+            uint32_t g_row = (uint32_t)(wt * (32 * TT) + rd_row) * (uint32_t)(q.ldd * 4) + (uint32_t)(wn * (32 * TN) * 4 + rd_chunk * 16);
+            const uint32_t g_step8 = 8u * (uint32_t)(q.ldd * 4);
 #pragma unroll
             for (int ti = 0; ti < TT; ++ti) {
-                if (ti) ep_row += ep_row_step;
-                asm volatile("" : "+v"(ep_row));
 #pragma unroll
                 for (int ni = 0; ni < TN; ++ni) {
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int rg = 0; rg < 4; ++rg) {
-                        const int c0 = ni * 32 + rg * 8;
-                        if (!full && wn * (32 * TN) + c0 >= cur.cols_left) continue;
-                        const float e0 = acc[ni][ti][rg * 4 + 0], e1 = acc[ni][ti][rg * 4 + 1];
-                        const float e2 = acc[ni][ti][rg * 4 + 2], e3 = acc[ni][ti][rg * 4 + 3];
-                        const f32x4 vf = {e0, e1, e2, e3};
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vf), rD, ep_row, c0 * 4, kStreamStoreAux);
+                        const f32x4 vf = {acc[ni][ti][rg * 4 + 0], acc[ni][ti][rg * 4 + 1], acc[ni][ti][rg * 4 + 2], acc[ni][ti][rg * 4 + 3]};
+                        const int chunk = 2 * rg + (eln >> 5);           // 16-byte piece of the row's 128 bytes
+                        *(u32x4*)(stag + st_wr + ((chunk ^ st_sw) << 4)) = __builtin_bit_cast(u32x4, vf);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int row = j * 8 + rd_row;
+                        const u32x4 v = *(const u32x4*)(stag + row * 128 + ((rd_chunk ^ ((row ^ (row >> 3)) & 7)) << 4));
+                        uint32_t off = g_row + (uint32_t)(ti * 4 + j) * g_step8;
+                        asm volatile("" : "+v"(off));
+                        const bool ok = full || wn * (32 * TN) + ni * 32 + rd_chunk * 4 < cur.cols_left;
+                        if (ok) __builtin_amdgcn_raw_buffer_store_b128(v, rD, off, ni * 128, kStreamStoreAux);
                     }
                 }
             }

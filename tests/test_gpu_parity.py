@@ -525,6 +525,25 @@ def test_full_size_config4_sampled_rows_and_whole_output():
     _whole_output_check(got32, w.c[:512], C64, w.d_h, w.H, offs, w.dtype, wl.F32, "v3 fp32 out, every element of 512 rows")
 
 
+@pytest.mark.parametrize("out_dtype", [None, wl.F32])
+def test_general_streaming_kernel_cut_tiles_over_several_rounds(out_dtype):
+    """Tile policy 3 (the general streaming kernel) on 32 x 12 tiles of 256 x 256, more than one per
+    workgroup, where each group's last tile is cut short by the group's end (1408 = 5.5 x 256 columns):
+    after such a tile fewer result stores are in flight than after a full one, which the next tile's
+    first load wait has to allow for.  Every element against a float64 library product, NaN-filled
+    output; 16-bit and float32 results (both staged through LDS)."""
+    w = wl.custom_kv_workload("cut_tiles", T=8192, d_c=512, d_h=128, H=[11, 11], std=0.02, rms_norm=True, dtype=wl.BF16, seed=21)
+    offs = [64, 384]
+    p = bda.bda_kv_project_plan(w.T, w.d_c, w.d_h, w.H, offs, w.dtype, out_dtype=out_dtype, tile_policy=3)
+    assert p["kernel"] == bda.KERNEL_STREAM and p["rounds"] >= 2, p
+    C_stored, C64 = _prepare_stored(w.W, w.d_c, w.H, w.d_h, offs, w.dtype)
+    od = w.dtype if out_dtype is None else out_dtype
+    got, _ = gh.kv_project(w.c_stored, C_stored, w.d_c, w.d_h, w.H, offs, w.dtype, out_dtype=out_dtype, fill=NAN_FILL[od], policy=3)
+    _whole_output_check(got, w.c, C64, w.d_h, w.H, offs, w.dtype, od, "cut tiles, general streaming kernel")
+    rows = _sample_rows(w.T, 24, seed=6)[:48]
+    assert_parity(got[rows], oracle.kv_project(w.c[rows], C64, w.d_h, w.H, offs), w.d_h, w.dtype, od, "cut tiles, oracle rows")
+
+
 def test_full_size_lowrank_sampled_rows_and_whole_output():
     """Config 5 (BD linear layer, T = 8192, fp16).  Three checks (Section "BD for Linear Layer"):
       1. end to end against the oracle, whose h = x U' is never rounded: the h block at the plain
