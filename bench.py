@@ -565,7 +565,8 @@ def main() -> int:
     # ------------------------------------------------------------------ CPU baseline: the oracle
     if not args.no_cpu_baseline:
         import oracle
-        probe = 8
+        probe = min(T, 128)                    # (a handful of tokens would not keep the oracle's threads busy and overestimate)
+        oracle.kv_project(w.c[:8], C64, d_h, H, offs)
         t0 = time.perf_counter()
         oracle.kv_project(w.c[:probe], C64, d_h, H, offs)
         per_tok = (time.perf_counter() - t0) / probe
