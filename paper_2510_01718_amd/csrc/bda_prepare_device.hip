@@ -267,27 +267,68 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
 template <typename WT, typename CT>
 __global__ __launch_bounds__(kPrepThreads) void side_kernel(const PrepArgs a)
 {
+    // Q: out[s, i] = sum_j W_q[s, col0 + j] W[off + i, col0 + j]      (d_side x d_h per head)
+    // O: out[i, m] = sum_j W[off + i, col0 + j] W_o[col0 + j, m]      (d_h x d_side per head)
+    // 64 x 64 output tiles, the contraction staged through LDS 16 at a time, 4 x 4 outputs per thread
+    // (rows ty + 16 u, columns tx + 16 v); workgroup (head, part) takes tiles part, part + gridDim.y, ...
+    // Each output is one sum in ascending j, whatever the grid.
+    constexpr int TS = 64, KC = 16;
+    __shared__ double As[TS][KC + 1];
+    __shared__ double Bs[KC][TS + 1];
     const int n = a.d_h, h = blockIdx.x, t = threadIdx.x;
     const int off = window_start(a);
     if (off < 0) return;
     const int64_t col0 = (int64_t)h * n;
-    if (a.side_kind == BDA_SIDE_Q) {
-        for (int s = blockIdx.y; s < a.d_side; s += gridDim.y)
-            for (int i = t; i < n; i += kPrepThreads) {
-                double acc = 0.0;
-                for (int j = 0; j < n; ++j)
-                    acc = fma(load_as_double<WT>(a.side, (int64_t)s * a.ld_side + col0 + j),
-                              load_as_double<WT>(a.W, (int64_t)(off + i) * a.ldw + col0 + j), acc);
-                store_rounded<CT>(a.side_out, (int64_t)s * a.ld_side_out + col0 + i, acc);
+    const bool q = a.side_kind == BDA_SIDE_Q;
+    const int R = q ? a.d_side : n, Cn = q ? n : a.d_side;
+    auto w = [&](int i, int j) { return load_as_double<WT>(a.W, (int64_t)(off + i) * a.ldw + col0 + j); };
+    const int tx = t % 16, ty = t / 16;
+    const int tiles_c = (Cn + TS - 1) / TS, n_tiles = ((R + TS - 1) / TS) * tiles_c;
+    for (int tile = blockIdx.y; tile < n_tiles; tile += gridDim.y) {
+        const int r0 = (tile / tiles_c) * TS, c0 = (tile % tiles_c) * TS;
+        double acc[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+        for (int j0 = 0; j0 < n; j0 += KC) {
+            for (int e = t; e < TS * KC; e += kPrepThreads) {
+                // both operands of Q and the first of O are contiguous along j; W_o is contiguous along m
+                const int rr = e / KC, jj = e % KC;
+                const bool okj = j0 + jj < n;
+                As[rr][jj] = (okj && r0 + rr < R) ? (q ? load_as_double<WT>(a.side, (int64_t)(r0 + rr) * a.ld_side + col0 + j0 + jj)
+                                                      : w(r0 + rr, j0 + jj)) : 0.0;
+                if (q) Bs[jj][rr] = (okj && c0 + rr < Cn) ? w(c0 + rr, j0 + jj) : 0.0;
             }
-    } else {
-        for (int i = blockIdx.y; i < n; i += gridDim.y)
-            for (int m = t; m < a.d_side; m += kPrepThreads) {
-                double acc = 0.0;
-                for (int j = 0; j < n; ++j)
-                    acc = fma(load_as_double<WT>(a.W, (int64_t)(off + i) * a.ldw + col0 + j),
-                              load_as_double<WT>(a.side, (col0 + j) * a.ld_side + m), acc);
-                store_rounded<CT>(a.side_out, (col0 + i) * a.ld_side_out + m, acc);
+            if (!q)
+                for (int e = t; e < TS * KC; e += kPrepThreads) {
+                    const int jj = e / TS, cc = e % TS;
+                    Bs[jj][cc] = (j0 + jj < n && c0 + cc < Cn) ? load_as_double<WT>(a.side, (col0 + j0 + jj) * a.ld_side + c0 + cc) : 0.0;
+                }
+            __syncthreads();
+#pragma unroll
+            for (int jj = 0; jj < KC; ++jj) {
+                double av[4], bv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) av[u] = As[ty + 16 * u][jj];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) bv[v] = Bs[jj][tx + 16 * v];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[u][v] = fma(av[u], bv[v], acc[u][v]);
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int r = r0 + ty + 16 * u, c = c0 + tx + 16 * v;
+                if (r < R && c < Cn) {
+                    if (q) store_rounded<CT>(a.side_out, (int64_t)r * a.ld_side_out + col0 + c, acc[u][v]);
+                    else store_rounded<CT>(a.side_out, (col0 + r) * a.ld_side_out + c, acc[u][v]);
+                }
             }
     }
 }
@@ -537,7 +578,11 @@ int run_prepare(const PrepCall& c, const Plan& p, unsigned char* ws, hipStream_t
     a.d_c = c.d_c; a.H = c.H; a.d_h = c.d_h; a.d_side = c.d_side; a.side_kind = c.side_kind;
     a.n_parts = p.n_parts;
     const bool multi = p.n_cand > 1;
-    const int side_parts = c.side_kind == BDA_SIDE_Q ? (c.d_side < 64 ? c.d_side : 64) : (c.d_h < 64 ? c.d_h : 64);
+    int side_parts = 1;                      // workgroups per head of the companion kernel: its 64 x 64 tiles, at most 64
+    if (c.side_kind != BDA_SIDE_NONE) {
+        const int64_t tiles = (int64_t)((c.d_side + 63) / 64) * ((c.d_h + 63) / 64);
+        side_parts = (int)(tiles < 64 ? tiles : 64);
+    }
     if (ws) {
         hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(kMaxCandidates), 0, st, flags, kMaxCandidates, 0);
         if (int rc = check_launch("fill kernel")) return rc;
