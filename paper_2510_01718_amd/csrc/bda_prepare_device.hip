@@ -188,6 +188,7 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
         for (int j = t; j < n; j += kPrepThreads) A[k * ld + j] = (j == k ? 1.0 : A[k * ld + j]) * inv;
         __syncthreads();
         if (row < n && row != k) {
+#pragma unroll 8
             for (int j = j_lo; j < j_hi; ++j) {
                 const double cur = (j == k) ? 0.0 : A[row * ld + j];
                 A[row * ld + j] = cur - f * A[k * ld + j];
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
 #pragma unroll
             for (int m = 0; m < kPrepRows; ++m) acc[m] = 0.0;
             if (n_rg == 2) {
+#pragma unroll 4
                 for (int k = 0; k < n; ++k) {
                     const double b = A[k * ld + j];
 #pragma unroll
@@ -245,6 +247,7 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
                     if (r < K) store_rounded<CT>(a.C, (int64_t)r * a.ldC + col0 + j, acc[m]);
                 }
             } else {
+#pragma unroll 4
                 for (int k = 0; k < n; ++k) {
                     const double b = A[k * ld + j];
 #pragma unroll
