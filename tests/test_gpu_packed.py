@@ -93,6 +93,15 @@ def test_packed_groups_ragged_tiles_and_pitches(T, dtype, out_dtype):
     _case(w, [56, 0], out_dtype=out_dtype)
 
 
+@pytest.mark.parametrize("T", [1, 64])
+def test_packed_v3_width(T):
+    # the V3-shaped weights of BASELINE configuration 4 (N = 32768, bf16) with a few tokens: 256 wide slices
+    w = wl.kv_workload("v3")
+    w = wl.KVWorkload(name="v3_decode", seed=w.seed, dtype=w.dtype, T=T, d_c=w.d_c, d_h=w.d_h, H=w.H,
+                      c_stored=w.c_stored[:T], c=w.c[:T], W=w.W)
+    _case(w, [0, 0], wide=True)
+
+
 def test_packed_wide_kernel_ragged_last_tile_and_odd_K():
     # 159 full slices of 128 columns and one of 96 in the first group, 32 in the second; K = 296: rows
     # past K in the wide kernel's last request must read as zeros, not as the next sub-slice's rows
