@@ -770,8 +770,9 @@ def test_prepare_device_storage_types(w_dtype, c_dtype):
     assert np.array_equal(Cs, want)
 
 
-def test_prepare_device_flags_singular_head_and_feeds_projection():
-    d_c, H, d_h = 128, 3, 32
+@pytest.mark.parametrize("d_h", [32, 64, 128])
+def test_prepare_device_flags_singular_head_and_feeds_projection(d_h):
+    d_c, H = 4 * d_h, 3
     w = wl.custom_kv_workload("prep", T=70, d_c=d_c, d_h=d_h, H=[H], std=0.125, rms_norm=False, dtype=wl.F16, seed=62)
     Wb = w.W.copy()
     Wb[5, d_h:2 * d_h] = Wb[9, d_h:2 * d_h]          # head 1: two equal rows inside the first window
