@@ -372,6 +372,12 @@ def main() -> int:
         t_again = bench_fixed(main_fn)
         extra["main_repeated_later"] = {"us": t_again * 1e6, "vs_first_measurement": t_again / kernel_s}
         log(f"main again: {t_again * 1e6:.2f} us")
+        # the same launch with float32 results (out_dtype = BDA_F32: twice the output bytes)
+        o32 = [torch.empty((T, N), dtype=torch.float32, device="cuda") for _ in range(R)]
+        t_32 = bench_fixed(lambda i, s: bda.bda_kv_project(c_bufs[i % R], d_c, T, d_c, d_h, H, offs, C_d, N, o32[i % R], N, w.dtype, wl.F32, s))
+        extra["main_f32_out"] = {"us": t_32 * 1e6, "tflops": flops / t_32 / 1e12, "store_gbs": T * N * 4.0 / t_32 / 1e9}
+        log(f"main with float32 results: {t_32 * 1e6:.2f} us, {T * N * 4.0 / t_32 / 1e9:.0f} GB/s of stores")
+        del o32
 
         # ---- the other large configuration (the V2-Lite shape when the main line is the V3 shape, and vice versa)
         other = "v2lite" if name == "v3" else "v3"
