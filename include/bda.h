@@ -287,11 +287,13 @@ int bda_kv_project_packed(const void* c, int64_t ldc, int64_t T, int d_c, int d_
  *       (contraction d_c - d_h <= 384), whatever the output width,
  *   6 = 128 x 256 tiles with the two-workgroups-per-compute-unit streaming kernel wherever it
  *       applies (16-bit types, every group's width a multiple of 256, d_c - d_h a multiple of 32,
- *       d_h 64 or 128), else automatic.
+ *       d_h 64 or 128), else automatic,
+ *   7 = 64 x 256 with the lean streaming kernel where it applies (else as 0 without the small-T
+ *       kernels).
  * bda_kv_project_backward_ex honours 1 (128 x 128 output tiles) and treats the rest as automatic.
  * Results do not depend on the policy beyond which kernel computes them (the order of the float32
  * summation over k is the same for every tile shape).  Errors: as the plain call, plus BDA_EINVAL
- * for a policy outside 0 .. 6.
+ * for a policy outside 0 .. 7.
  */
 int bda_kv_project_ex(const void* c, int64_t ldc, int64_t T, int d_c, int d_h,
                       int G, const int* H, const int* basis_offset,
@@ -318,7 +320,7 @@ typedef enum {
     BDA_KERNEL_GENERAL = 1, /* any type / shape / alignment: 64 x 64 tiles, float32 FMA */
     BDA_KERNEL_MFMA = 2,    /* register-staged MFMA kernel, 128 x 128 or 256 x 256 tiles */
     BDA_KERNEL_STREAM = 3,  /* streaming MFMA kernel (LDS DMA ring), general variant */
-    BDA_KERNEL_LEAN = 4,    /* streaming MFMA kernel, lean variant (256- or 128-token tiles) */
+    BDA_KERNEL_LEAN = 4,    /* streaming MFMA kernel, lean variant (256-, 128- or 64-token tiles) */
     BDA_KERNEL_DECODE = 5,  /* few tokens (token tiles of up to 128): weight-streaming kernels; tile_columns tells 32-, 64- and 128-column slices apart */
     BDA_KERNEL_DUO = 6      /* streaming MFMA kernel, two 4-wave workgroups per compute unit, 128 x 256 tiles */
 } bda_kernel_id;

@@ -65,16 +65,20 @@ int launch_mfma(GemmArgs& a, hipStream_t st)
 constexpr int kStreamSK = 64, kStreamNS = 2;
 
 // Streaming kernel; `plain` selects its lean variant (every stage of every tile free of per-lane
-// decisions: see bda_gemm_plain.hpp), `half_tokens` the lean variant with 128-token tiles.
+// decisions: see bda_gemm_plain.hpp), `tok_tile` = 128 or 64 the lean variant with tiles of that many
+// tokens (256: the full tile).
 template <typename X, typename OutT>
-int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
+int launch_stream(GemmArgs& a, bool plain, int tok_tile, hipStream_t st)
 {
-    static LdsLimitState once, once_plain, once_half;
+    static LdsLimitState once, once_plain, once_half, once_quarter;
+    const bool half_tokens = tok_tile == 128, quarter_tokens = tok_tile == 64;
     constexpr int lds = kStreamNS * (256 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
     constexpr int lds_half = kStreamNS * (128 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
+    constexpr int lds_quarter = kStreamNS * (64 * 2 * kStreamSK + kStreamSK * 512) + 8 * 4096;
     auto kern = gemm_stream_kernel<X, OutT, 2, 4, kStreamSK, kStreamNS>;
     auto kern_plain = gemm_plain_kernel<X, OutT, 4>;
     auto kern_half = gemm_plain_kernel<X, OutT, 2>;
+    auto kern_quarter = gemm_plain_kernel<X, OutT, 1>;
     a.n_super_m = (a.m_tiles + a.sm - 1) / a.sm;
     a.n_super_n = (a.n_tiles + a.sn - 1) / a.sn;
     a.dh_magic = a.d_h > 0 ? (((uint64_t)1 << 40) + a.d_h - 1) / a.d_h : 0;
@@ -82,7 +86,7 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
     int64_t total = (int64_t)a.n_super_m * a.n_super_n;      // super-tiles
     int64_t per_die = (total + kNumXcd - 1) / kNumXcd;
     a.rounds = (int)per_die;
-    if (plain || half_tokens) {
+    if (plain || half_tokens || quarter_tokens) {
         // Tile-by-tile order (lean kernel only) where it needs fewer rounds than whole super-tiles:
         // small grids whose shape does not factor into 8 dies x (sm x sn) slots.
         const int64_t tiles = (int64_t)a.m_tiles * a.n_tiles;
@@ -110,11 +114,13 @@ int launch_stream(GemmArgs& a, bool plain, bool half_tokens, hipStream_t st)
         a.xcd_count[x] = (int)std::min<int64_t>(per_die, total - first);
     }
     const int wgs_per_die = a.lin_slots ? a.lin_slots : a.sm * a.sn;
-    if (plan_only(a, plain || half_tokens ? BDA_KERNEL_LEAN : BDA_KERNEL_STREAM, half_tokens ? 128 : 256, 256,
-                  kNumXcd * wgs_per_die, 512, half_tokens ? lds_half : lds, a.rounds)) return BDA_OK;
-    if (int rc = half_tokens ? set_max_lds(kern_half, lds_half, once_half)
+    if (plan_only(a, plain || half_tokens || quarter_tokens ? BDA_KERNEL_LEAN : BDA_KERNEL_STREAM, quarter_tokens ? 64 : half_tokens ? 128 : 256, 256,
+                  kNumXcd * wgs_per_die, 512, quarter_tokens ? lds_quarter : half_tokens ? lds_half : lds, a.rounds)) return BDA_OK;
+    if (int rc = quarter_tokens ? set_max_lds(kern_quarter, lds_quarter, once_quarter)
+                 : half_tokens ? set_max_lds(kern_half, lds_half, once_half)
                  : plain ? set_max_lds(kern_plain, lds, once_plain) : set_max_lds(kern, lds, once)) return rc;
-    if (half_tokens) hipLaunchKernelGGL(kern_half, dim3(kNumXcd * wgs_per_die), dim3(512), lds_half, st, a);
+    if (quarter_tokens) hipLaunchKernelGGL(kern_quarter, dim3(kNumXcd * wgs_per_die), dim3(512), lds_quarter, st, a);
+    else if (half_tokens) hipLaunchKernelGGL(kern_half, dim3(kNumXcd * wgs_per_die), dim3(512), lds_half, st, a);
     else if (plain) hipLaunchKernelGGL(kern_plain, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
     else hipLaunchKernelGGL(kern, dim3(kNumXcd * wgs_per_die), dim3(512), lds, st, a);
     hipError_t err = hipGetLastError();
@@ -407,12 +413,17 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
             if (dtype == BDA_BF16 && out_dtype == BDA_BF16) return launch_duo<BF16, uint16_t>(a, st);
             if (dtype == BDA_BF16 && out_dtype == BDA_F32) return launch_duo<BF16, float>(a, st);
         }
-        const bool half_tokens = plain && (policy == 4 || (policy == 0 && 0.56 * (double)rounds_of(mt128 * nt256) < (double)rounds_of(mt256 * nt256)));
-        const bool big = plain || policy == 2 || policy == 3 || policy == 4 || (policy == 0 && mt256 * nt256 >= 96);
+        // Its 64-token tile costs 0.47-0.5 of the 256-token tile per round, less than the 128-token tile, but
+        // two rounds of it cost more than one of either: it is taken where one round of it covers the launch.
+        const int64_t mt64 = (a.M + 63) / 64;
+        const bool quarter_tokens = plain && (policy == 7 || (policy == 0 && rounds_of(mt64 * nt256) == 1));
+        const bool half_tokens = plain && !quarter_tokens && (policy == 4 || (policy == 0 && 0.56 * (double)rounds_of(mt128 * nt256) < (double)rounds_of(mt256 * nt256)));
+        const int tok_tile = quarter_tokens ? 64 : half_tokens ? 128 : 256;
+        const bool big = plain || policy == 2 || policy == 3 || policy == 4 || ((policy == 0 || policy == 7) && mt256 * nt256 >= 96);
         const bool stream = big && stream_ok;
         if (big) {
-            build_tiles(a, G, group_cols, half_tokens ? 128 : 256, 256);
-            choose_super(a, kSlotsPerXcd, half_tokens ? 128 : 256, 256);
+            build_tiles(a, G, group_cols, tok_tile, 256);
+            choose_super(a, kSlotsPerXcd, tok_tile, 256);
             // identity slice: stages of the streaming kernel (the slice of a 256-column tile is the
             // whole window, or the tile's own 256 columns of it when d_h is a multiple of 256)
             a.n_stage_id = plain ? n_stage_id_lean : n_stage_id;
@@ -421,7 +432,7 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
             choose_super(a, 2 * kSlotsPerXcd, 128, 128);
         }
 #define BDA_LAUNCH(X, O)                                      \
-    return stream ? launch_stream<X, O>(a, plain, half_tokens, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
+    return stream ? launch_stream<X, O>(a, plain, plain ? tok_tile : 256, st) : big ? launch_mfma<X, O, 4, 4>(a, st) : launch_mfma<X, O, 2, 2>(a, st)
         if (dtype == BDA_F16 && out_dtype == BDA_F16) { BDA_LAUNCH(F16, uint16_t); }
         if (dtype == BDA_F16 && out_dtype == BDA_F32) { BDA_LAUNCH(F16, float); }
         if (dtype == BDA_BF16 && out_dtype == BDA_BF16) { BDA_LAUNCH(BF16, uint16_t); }
@@ -456,7 +467,7 @@ PolicyScope::~PolicyScope() { t_policy = prev_; }
 
 int check_policy(const char* fn, int policy)
 {
-    return policy >= 0 && policy <= 6 ? BDA_OK : fail(BDA_EINVAL, "%s: tile_policy must be 0 .. 6 (got %d)", fn, policy);
+    return policy >= 0 && policy <= 7 ? BDA_OK : fail(BDA_EINVAL, "%s: tile_policy must be 0 .. 7 (got %d)", fn, policy);
 }
 
 }  // namespace bda

@@ -37,14 +37,14 @@ template <typename X, typename OutT, int TT_ = 4>
 __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 {
     constexpr int SK = 64, WN = 4, NW = 8;
-    constexpr int TT = TT_, TN = 2;           // TT = 4: 256-token tiles; TT = 2: 128-token tiles
+    constexpr int TT = TT_, TN = 2;           // TT = 4: 256-token tiles; TT = 2: 128-token tiles; TT = 1: 64-token tiles
     constexpr int BT = 64 * TT, BN = 256;
     constexpr int PR = SK / 8, RB = SK * 2, RPI = 64 / PR, KS = SK / 16;
     constexpr int PIT = BT / RPI / NW, PIW = SK / 2 / NW;
     constexpr int TOK_BYTES = BT * RB;
     constexpr int STAGE_BYTES = TOK_BYTES + SK * BN * 2;
     constexpr int STORES = TT * TN * (sizeof(OutT) == 4 ? 4 : 2);
-    static_assert((TT == 4 || TT == 2) && PIT == TT && PIW == 4 && STAGE_BYTES % 1024 == 0, "layout constants of this variant");
+    static_assert((TT == 4 || TT == 2 || TT == 1) && PIT == TT && PIW == 4 && STAGE_BYTES % 1024 == 0, "layout constants of this variant");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     struct {
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
 #pragma unroll
     for (int j = 0; j < PIT; ++j)
         vo_tok[j] = (uint32_t)(wave * (RPI * PIT) + lane / PR + RPI * j) * tok_row_bytes
-                    + (uint32_t)(((lane % PR) ^ tok_swz<SK>((lane / PR + RPI * j) & 15)) * 16);
+                    + (uint32_t)(((lane % PR) ^ tok_swz<SK>((wave * (RPI * PIT) + lane / PR + RPI * j) & 15)) * 16);   // (the row's own low bits: a wave of the 64-token variant owns 8 rows)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
         vo_wgt[j] = (uint32_t)(wave * (2 * PIW) + (lane >> 5)) * wgt_row_bytes + (uint32_t)(((lane & 31) ^ wgt_swz(2 * j + (lane >> 5))) * 16);
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             asm volatile("" : "+v"(ln));
 #pragma unroll
             for (int j = 0; j < PIT; ++j) {
-                const int x = ((ln % PR) ^ tok_swz<SK>((ln / PR + RPI * j) & 15)) * 8;   // first k of the lane's piece, within the stage
+                const int x = ((ln % PR) ^ tok_swz<SK>((wave * (RPI * PIT) + ln / PR + RPI * j) & 15)) * 8;   // first k of the lane's piece, within the stage
                 if (x >= e) vt[j] += skip_bytes;
             }
         }
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
     };
     // The four loads of a stage that go to the weight half of the slot: rows of the weight tile, or
     // (identity stage) the second 64 window columns of the token rows.  Uniform choice per stage.
-    // (With 128-token tiles the second token set has two loads per wave; the other two keep the
+    // (With 128-token tiles the second token set has two loads per wave, with 64-token tiles one; the others keep the
     // stage's load count and write zeros to the unused part of the weight half, 2 KiB per wave.)
     auto slot_of = [&](uint32_t lds_b) { return lds_b - (uint32_t)wave * 4096u; };   // slot start (absolute LDS address)
     struct Second { u32x4 r; uint32_t base, base_unused; uint32_t so, so_step; uint32_t v[4]; };
@@ -395,11 +395,15 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 2>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw0[1], ft0[2], acc[1][2]); acc[1][3] = mm(fw0[1], ft0[3], acc[1][3]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 3>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
-        } else {
+        } else if constexpr (TT == 2) {
             acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]); acc[0][1] = mm(fw0[0], ft0[1], acc[0][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]); acc[1][1] = mm(fw0[1], ft0[1], acc[1][1]);
             __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 1>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
+        } else {
+            acc[0][0] = mm(fw0[0], ft0[0], acc[0][0]);
+            __builtin_amdgcn_sched_barrier(0); tok_load(std::integral_constant<int, 0>{}, pt, lds_b, ts, vt); __builtin_amdgcn_sched_barrier(0);
+            acc[1][0] = mm(fw0[1], ft0[0], acc[1][0]);
         }
         // first fragments of the next stage, out of the other slot
         if (next_regular) read_w(0, fw0);
@@ -413,7 +417,7 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][2] = mm(fw1[1], ft1[2], acc[1][2]); acc[1][3] = mm(fw1[1], ft1[3], acc[1][3]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
-        } else {
+        } else if constexpr (TT == 2) {
             acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[0][1] = mm(fw1[0], ft1[1], acc[0][1]);
@@ -422,6 +426,11 @@ __global__ __launch_bounds__(512) void gemm_plain_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); __builtin_amdgcn_sched_barrier(0);
             acc[1][1] = mm(fw1[1], ft1[1], acc[1][1]);
             __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
+        } else {
+            acc[0][0] = mm(fw1[0], ft1[0], acc[0][0]);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 0>{}, z); wgt_load(std::integral_constant<int, 1>{}, z); __builtin_amdgcn_sched_barrier(0);
+            acc[1][0] = mm(fw1[1], ft1[0], acc[1][0]);
+            __builtin_amdgcn_sched_barrier(0); wgt_load(std::integral_constant<int, 2>{}, z); wgt_load(std::integral_constant<int, 3>{}, z); __builtin_amdgcn_sched_barrier(0);
         }
         slot_b = (uint32_t)STAGE_BYTES - slot_b;
     };

@@ -147,7 +147,7 @@ def test_tile_kernels_random_shapes(seed):
         c_stored, c64 = wl.to_storage(rng.standard_normal((T, d_c)), dtype)
         C_stored, C64 = wl.to_storage(rng.standard_normal((K, N)) * 0.2, dtype)
         ref = oracle.kv_project(c64, C64, d_h, H, offs)
-        for policy in (0, 1, 2, 3, 4, 5, 6):
+        for policy in (0, 1, 2, 3, 4, 5, 6, 7):
             what = f"seed {seed} case {case} policy {policy}: T={T} d_c={d_c} d_h={d_h} H={H} offs={offs} ld=({ldc},{ldC},{ld_out})"
             got, _ = gh.kv_project(c_stored, C_stored, d_c, d_h, H, offs, dtype, ldc=ldc, ldC=ldC, ld_out=ld_out, fill=-7.0,
                                    policy=policy)
@@ -198,7 +198,7 @@ def test_kv_medium_ragged(policy, dtype, offs):
     _run_kv_case(w, offs, policy=policy)
 
 
-@pytest.mark.parametrize("policy", [2, 3, 4, 6])
+@pytest.mark.parametrize("policy", [2, 3, 4, 6, 7])
 @pytest.mark.parametrize("dtype,out_dtype", [(wl.F16, None), (wl.BF16, None), (wl.F16, wl.F32)])
 @pytest.mark.parametrize("offs", [[0, 0], [384, 384], [64, 192], [16, 208], [8, 376], [120, 72]])
 def test_kv_lean_and_general_streaming_kernels(policy, dtype, out_dtype, offs):
@@ -212,7 +212,7 @@ def test_kv_lean_and_general_streaming_kernels(policy, dtype, out_dtype, offs):
     _run_kv_case(w, offs, out_dtype=out_dtype, policy=policy)
 
 
-@pytest.mark.parametrize("policy", [2, 4, 6])
+@pytest.mark.parametrize("policy", [2, 4, 6, 7])
 def test_kv_lean_three_groups(policy):
     """Three groups with different windows through the lean kernel (group look-up beyond the two
     register-held groups)."""
@@ -229,7 +229,7 @@ def test_kv_lean_tile_by_tile_order_two_rounds():
     _run_kv_case(w, [0, 384], policy=4)
 
 
-@pytest.mark.parametrize("policy", [2, 3, 4, 6])
+@pytest.mark.parametrize("policy", [2, 3, 4, 6, 7])
 @pytest.mark.parametrize("d_c,d_h,H,offs", [(256, 64, [8, 4], [0, 192]),        # window narrower than an identity stage
                                             (448, 192, [4], [64]),              # one and a half identity stages
                                             (512, 256, [2, 1], [256, 0]),       # window = tile width: two stages
@@ -242,18 +242,19 @@ def test_kv_lean_head_widths(policy, d_c, d_h, H, offs):
     _run_kv_case(w, offs, policy=policy)
 
 
-@pytest.mark.parametrize("T", [600, 1300, 1536])
-def test_kv_lean_automatic_tile_choice(T):
-    """Automatic policy on the V2-Lite shape at token counts that select 128-token tiles
-    (tile-by-tile order at 1536: 12 x 16 tiles)."""
+@pytest.mark.parametrize("T,tile", [(600, 64), (1024, 64), (1300, 128), (1536, 128)])
+def test_kv_lean_automatic_tile_choice(T, tile):
+    """Automatic policy on the V2-Lite shape at token counts that select 64-token tiles (one round of
+    them covers the launch) and 128-token tiles (tile-by-tile order at 1536: 12 x 16 tiles)."""
     w = wl.custom_kv_workload("auto", T=T, d_c=512, d_h=128, H=[16, 16], std=0.02, rms_norm=True,
                               dtype=wl.F16, seed=23)
     p = bda.bda_kv_project_plan(T, 512, 128, [16, 16], [0, 0], wl.F16)
-    assert (p["kernel"], p["tile_tokens"]) == (bda.KERNEL_LEAN, 128)
+    assert (p["kernel"], p["tile_tokens"]) == (bda.KERNEL_LEAN, tile)
     _run_kv_case(w, [0, 0])
+    _run_kv_case(w, [64, 200])                               # windows inside the latent, one off the 64-column stage grid
 
 
-@pytest.mark.parametrize("policy", [2, 3, 4, 6])
+@pytest.mark.parametrize("policy", [2, 3, 4, 6, 7])
 def test_dense_many_stages_streaming(policy):
     """A long contraction (K = 1024: 16 stages per tile, no identity slice) through both streaming kernels."""
     rng = np.random.default_rng(13)

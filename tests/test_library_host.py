@@ -223,11 +223,11 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert pk(fake, 96, 4, 96, 32, 1, H32, off, far, fake, 64, 1, 1, None) == -1 and b"overlaps" in lib.bda_last_error()
     assert pk(fake, 100, 4, 96, 32, 1, H32, off, far, farther, 64, 1, 1, None) == -1 and b"canonical" in lib.bda_last_error()
     assert pk(None, 96, 0, 96, 32, 1, H32, off, None, None, 64, 1, 1, None) == 0
-    # a tile policy outside 0 .. 6 is refused before anything else is looked at
-    assert lib.bda_kv_project_ex(fake, 64, 4, 64, 16, 1, H, off, fake, 32, far, 32, 1, 1, None, 7) == -1
+    # a tile policy outside 0 .. 7 is refused before anything else is looked at
+    assert lib.bda_kv_project_ex(fake, 64, 4, 64, 16, 1, H, off, fake, 32, far, 32, 1, 1, None, 8) == -1
     assert b"tile_policy" in lib.bda_last_error()
     assert lib.bda_dense_project_ex(fake, 64, 4, 64, fake, 32, 32, far, 32, 1, 1, None, -1) == -1
-    assert lib.bda_kv_project_backward_ex(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None, 7) == -1
+    assert lib.bda_kv_project_backward_ex(None, 64, None, 32, None, 32, 4, 64, 16, 1, H, off, None, 64, None, 32, 1, 1, None, 8) == -1
 
 
 def test_workload_recipe_is_stable():
@@ -293,9 +293,10 @@ def test_launch_plan_benchmark_shapes():
 
 
 def test_launch_plan_tile_choice_by_rounds():
-    """128-token tiles where they need fewer than 1/0.56 times the rounds of 256-token tiles; dies
-    take single tiles where whole super-tiles would need more rounds."""
-    want = {600: (128, 1, 1), 1024: (128, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
+    """64-token tiles where one round of them covers the launch; 128-token tiles where they need fewer
+    than 1/0.56 times the rounds of 256-token tiles; dies take single tiles where whole super-tiles
+    would need more rounds."""
+    want = {600: (64, 1, 1), 1024: (64, 1, 0), 1536: (128, 1, 1), 2048: (128, 1, 0), 2560: (256, 1, 1),
             3072: (256, 1, 1), 4096: (256, 1, 0), 5120: (128, 3, 0), 8192: (256, 2, 0)}
     for T, (tokens, rounds, by_tile) in want.items():
         p = _plan(T, [16, 16], [0, 0], bda.BDA_F16)
@@ -328,6 +329,10 @@ def test_launch_plan_preconditions_of_the_lean_kernel():
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=1)["kernel"] == bda.KERNEL_MFMA
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=3)["kernel"] == bda.KERNEL_STREAM
     assert _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=4)["tile_tokens"] == 128
+    p = _plan(4096, [16, 16], [0, 0], bda.BDA_F16, tile_policy=7)
+    assert (p["kernel"], p["tile_tokens"], p["rounds"], p["lds_bytes"]) == (bda.KERNEL_LEAN, 64, 4, 112 * 1024)
+    p = _plan(256, [128], [0], bda.BDA_BF16)                                 # V3 k_proj, 256 tokens: one round of 64-token tiles
+    assert (p["kernel"], p["tile_tokens"], p["workgroups"], p["rounds"]) == (bda.KERNEL_LEAN, 64, 256, 1)
     duo = _plan(8192, [128, 128], [0, 0], bda.BDA_BF16, tile_policy=6)       # two 4-wave workgroups per compute unit
     assert (duo["kernel"], duo["tile_tokens"], duo["workgroups"], duo["threads"], duo["rounds"]) == (bda.KERNEL_DUO, 128, 512, 256, 16)
     assert (duo["super_m"], duo["super_n"]) == (1, 8)                          # eight column ranges: one die keeps 16 column tiles of weights
