@@ -89,9 +89,14 @@ def test_small_T_kernels_with_token_tiles(T, dtype, out_dtype):
     assert (p["kernel"], p["tile_columns"], p["token_tiles"]) == (bda.KERNEL_DECODE, 32, (T + 127) // 128)
     _run_kv_case(w, [72, 384], out_dtype=out_dtype)
     if T <= 256:
+        # (group widths off the 256-column grid; where the lean kernel applies, one round of its 64-token tiles is taken instead)
+        w = wl.custom_kv_workload("tiles64", T=T, d_c=512, d_h=128, H=[33, 31], std=0.02, rms_norm=True, dtype=dtype, seed=71 + T)
+        p = bda.bda_kv_project_plan(T, 512, 128, [33, 31], [0, 200], dtype, out_dtype=out_dtype)
+        assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 64, 2, 256)
+        _run_kv_case(w, [0, 200], out_dtype=out_dtype)
         w = wl.custom_kv_workload("tiles64", T=T, d_c=512, d_h=128, H=[34, 30], std=0.02, rms_norm=True, dtype=dtype, seed=71 + T)
         p = bda.bda_kv_project_plan(T, 512, 128, [34, 30], [0, 200], dtype, out_dtype=out_dtype)
-        assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 64, 2, 256)
+        assert (p["kernel"], p["tile_tokens"], p["rounds"]) == (bda.KERNEL_LEAN, 64, 1)
         _run_kv_case(w, [0, 200], out_dtype=out_dtype)
 
 

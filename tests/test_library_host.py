@@ -276,8 +276,10 @@ def test_launch_plan_benchmark_shapes():
     # more than 128 tokens: token tiles of 128 while all the workgroups fit the chip at once
     p = _plan(256, [16, 16], [0, 0], bda.BDA_F16)
     assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 32, 2, 256)
-    p = _plan(512, [16, 16], [0, 0], bda.BDA_F16)
+    p = _plan(512, [15, 17], [0, 0], bda.BDA_F16)                       # (group widths off the 256 grid: no lean kernel)
     assert (p["kernel"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_DECODE, 64, 4, 256)
+    p = _plan(512, [16, 16], [0, 0], bda.BDA_F16)                       # where the lean kernel applies: one round of its 64-token tiles
+    assert (p["kernel"], p["tile_tokens"], p["tile_columns"], p["token_tiles"], p["workgroups"]) == (bda.KERNEL_LEAN, 64, 256, 8, 128)
     assert _plan(600, [16, 16], [0, 0], bda.BDA_F16)["kernel"] == bda.KERNEL_LEAN
     p = _plan(64, [128, 128], [0, 0], bda.BDA_BF16)                     # wide output: 128-column slices
     assert (p["kernel"], p["tile_columns"], p["workgroups"], p["lds_bytes"]) == (bda.KERNEL_DECODE, 128, 256, 144 * 1024)
