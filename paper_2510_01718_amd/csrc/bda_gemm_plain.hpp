@@ -6,12 +6,13 @@
 // that changes from stage to stage is uniform:
 //   * the vector offset of each of a wave's eight loads never changes; the stage's column / row
 //     offset travels in the load's scalar offset;
-//   * the LDS addresses of the fragment reads flip between the two stage slots with one XOR each.
+//   * the LDS addresses of the fragment reads flip between the two stage slots with one addition each.
 // Counters on the general kernel showed it to be bound by instruction issue (about 340 instructions
 // per wave and stage for 32 MFMAs, a third of them scalar bookkeeping); this variant brings a stage
 // down to the MFMAs, the 32 LDS reads, the 8 loads and a few dozen scalar operations.
 // Same tile order, pipeline, swizzles and epilogue as the streaming kernel; SK = 64, two slots,
-// eight waves (2 x 4, 128 tokens x 64 columns each).
+// eight waves (2 x 4).  Three tile heights share the code: 256 tokens (128 tokens x 64 columns per
+// wave), 128 and 64 tokens (64 and 32 tokens per wave); the column width is 256 in all of them.
 #pragma once
 #include <type_traits>
 

@@ -226,6 +226,19 @@ def test_kv_lean_three_groups(policy):
     _run_kv_case(w, [0, 64, 384], policy=policy)
 
 
+@pytest.mark.parametrize("out_dtype", [None, wl.F32])
+@pytest.mark.parametrize("d_c,d_h,H,offs", [(512, 128, [10, 6], [64, 200]),     # seven stages per tile
+                                            (256, 64, [20, 12], [0, 192]),      # four
+                                            (256, 128, [10, 6], [0, 128])])     # three: the fewest the lean kernel takes
+def test_kv_lean_64_token_tiles_over_two_rounds(d_c, d_h, H, offs, out_dtype):
+    """Tile policy 7 on 33 x 8 tiles of 64 x 256: two rounds, the second nearly empty, ragged last token tile
+    (by itself the library takes 64-token tiles only where one round covers the launch)."""
+    w = wl.custom_kv_workload("lean64", T=2100, d_c=d_c, d_h=d_h, H=H, std=0.02, rms_norm=True, dtype=wl.BF16, seed=24)
+    p = bda.bda_kv_project_plan(w.T, d_c, d_h, H, offs, w.dtype, out_dtype=out_dtype or w.dtype, tile_policy=7)
+    assert (p["kernel"], p["tile_tokens"], p["rounds"]) == (bda.KERNEL_LEAN, 64, 2)
+    _run_kv_case(w, offs, out_dtype=out_dtype, policy=7)
+
+
 def test_kv_lean_tile_by_tile_order_two_rounds():
     """17 x 25 tiles of 128 x 256: whole super-tiles would need three rounds, so the tiles are dealt
     out one by one (54 per die, two rounds, the last die's run shorter); ragged last token tile."""
@@ -605,6 +618,7 @@ def test_full_size_lowrank_sampled_rows_and_whole_output():
     (300, 512, 128, [4, 2], [64, 192], wl.BF16, 2, "lean256"),
     (300, 512, 128, [4, 2], [64, 192], wl.F16, 3, "stream256"),
     (300, 512, 128, [4, 2], [64, 192], wl.BF16, 4, "lean128"),
+    (300, 512, 128, [4, 2], [64, 192], wl.F16, 7, "lean64"),
     (77, 52, 20, [2, 3], [3, 32], wl.F16, 0, "general"),
     (64, 64, 16, [2], [0], wl.F32, 0, "general fp32"),
 ])
