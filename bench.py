@@ -564,6 +564,39 @@ def main() -> int:
             torch.cuda.synchronize()
             prep[f"device_v2lite_layer_k_and_v_with_companions_{mname}_ms"] = (time.perf_counter() - t0) * 1e3
             assert int(flag.item()) == 0 and int(off_l.item()) >= 0
+        # A whole model's worth: 27 such layers, offset search, layer l on stream l mod 8 with outputs and a workspace
+        # per stream (one search keeps 16 of the 256 compute units busy in its inversions; the calls share nothing,
+        # so independent projections overlap; a process has four hardware queues here and the runtime deals streams
+        # out to them in turn, so eight streams cover all four whatever other streams the process has made).
+        mode = bda.BASIS_OFFSET_SEARCH
+        nb = bda.bda_prepare_device_workspace_bytes(d_c, Hl, d_h, mode, True)
+        lanes = []
+        for _ in range(8):
+            lanes.append(dict(stream=torch.cuda.Stream(), C=torch.empty_like(Cl), Sq=torch.empty_like(Sq), So=torch.empty_like(So),
+                              off=torch.zeros(2, dtype=torch.int32, device="cuda"), res=torch.zeros(6, dtype=torch.float64, device="cuda"),
+                              flag=torch.zeros(2, dtype=torch.int32, device="cuda"),
+                              ws=[torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(2)]))
+
+        def model(n_layers):
+            for layer_no in range(n_layers):
+                b = lanes[layer_no % 8]
+                s = int(b["stream"].cuda_stream)
+                bda.bda_prepare_device_ex(Wl, Hl * d_h, wl.F32, d_c, Hl, d_h, b["C"], Hl * d_h, wl.F16, side=Wq_l, ld_side=Hl * d_h,
+                                          d_side=d_model, side_kind=bda.SIDE_Q, side_out=b["Sq"], ld_side_out=Hl * d_h, mode=mode,
+                                          basis_offset_out=b["off"][:1], resid_out=b["res"][:3], singular_head=b["flag"][:1],
+                                          workspace=b["ws"][0], workspace_bytes=nb, stream=s)
+                bda.bda_prepare_device_ex(Wl, Hl * d_h, wl.F32, d_c, Hl, d_h, b["C"], Hl * d_h, wl.F16, side=Wo_l, ld_side=d_model,
+                                          d_side=d_model, side_kind=bda.SIDE_O, side_out=b["So"], ld_side_out=d_model, mode=mode,
+                                          basis_offset_out=b["off"][1:], resid_out=b["res"][3:], singular_head=b["flag"][1:],
+                                          workspace=b["ws"][1], workspace_bytes=nb, stream=s)
+        model(8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        model(27)
+        torch.cuda.synchronize()
+        prep["device_v2lite_model_27_layers_offset_search_8_streams_s"] = time.perf_counter() - t0
+        assert all(int(b["flag"].sum().item()) == 0 for b in lanes)
+        del lanes
         extra["prepare"] = prep
         log("prepare: " + ", ".join(f"{k} {v:.3g}" for k, v in prep.items()))
     result["extra"] = extra

@@ -149,3 +149,37 @@ def test_prepare_device_ex_singular_windows():
     assert np.max(np.abs(got["C"] - wl.to_storage(C_ref, wl.F16)[1])) <= 2.0 ** -10 * np.max(np.abs(C_ref))
     got = _run(W1, d_c, H, d_h, wl.F16, mode=oracle.FIRST)
     assert got["flag"] == 3 and np.all(got["C"][:, 2 * d_h:] == FILL) and not np.any(got["C"][:, :2 * d_h] == FILL)
+
+
+def test_prepare_device_ex_calls_overlapping_on_several_streams():
+    """Searches for different projections issued on four streams at once, each with a workspace and outputs of
+    its own (the calls share nothing else): every one gives what it gives alone on one stream, bit for bit."""
+    d_c, H, d_h, d_side = 192, 4, 64, 96
+    jobs = []
+    for j in range(8):
+        W, Wq, Wo = _weights(d_c, H, d_h, d_side, seed=700 + j, weak_first=(j % 2 == 0))
+        kind = oracle.SIDE_Q if j % 2 == 0 else oracle.SIDE_O
+        jobs.append((W, Wq if kind == oracle.SIDE_Q else Wo, kind))
+    alone = [_run(W, d_c, H, d_h, wl.F16, side, kind, oracle.OFFSET_SEARCH) for W, side, kind in jobs]
+    N = H * d_h
+    need = bda.bda_prepare_device_workspace_bytes(d_c, H, d_h, oracle.OFFSET_SEARCH, True)
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    bufs = []
+    for W, side, kind in jobs:
+        bufs.append(dict(W=torch.from_numpy(np.ascontiguousarray(W)).cuda(), side=torch.from_numpy(np.ascontiguousarray(side)).cuda(),
+                         C=torch.full((d_c - d_h, N), FILL, dtype=torch.float16, device="cuda"),
+                         side_out=torch.full(side.shape, FILL, dtype=torch.float16, device="cuda"),
+                         off=torch.full((1,), -99, dtype=torch.int32, device="cuda"), resid=torch.zeros(3, dtype=torch.float64, device="cuda"),
+                         flag=torch.zeros(1, dtype=torch.int32, device="cuda"), ws=torch.full((need,), 0x5A, dtype=torch.uint8, device="cuda")))
+    torch.cuda.synchronize()
+    for rep in range(3):                                   # three waves of eight calls, two per stream, nothing waits in between
+        for j, ((W, side, kind), b) in enumerate(zip(jobs, bufs)):
+            bda.bda_prepare_device_ex(b["W"], N, wl.F64, d_c, H, d_h, b["C"], N, wl.F16, side=b["side"], ld_side=side.shape[1], d_side=d_side,
+                                      side_kind=kind, side_out=b["side_out"], ld_side_out=side.shape[1], mode=oracle.OFFSET_SEARCH,
+                                      basis_offset_out=b["off"], resid_out=b["resid"], singular_head=b["flag"], workspace=b["ws"],
+                                      workspace_bytes=need, stream=int(streams[j % 4].cuda_stream))
+    torch.cuda.synchronize()
+    for j, (b, ref) in enumerate(zip(bufs, alone)):
+        assert int(b["flag"].item()) == 0 and int(b["off"].item()) == ref["off"], j
+        assert np.array_equal(_host(b["C"], wl.F16), ref["C"]) and np.array_equal(_host(b["side_out"], wl.F16), ref["side"]), j
+        assert np.array_equal(b["resid"].cpu().numpy(), ref["resid"]), j
