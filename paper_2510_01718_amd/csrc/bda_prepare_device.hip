@@ -1,7 +1,8 @@
 // GPU preparation of one projection (Algorithm "BD Attention Preparation (QK)", Appendix "BD for VO in
 // MHA", Algorithm "BD Decomposition (Row)" for the window choice, Appendix "Residual-Min with Offset
 // Search" for the candidate windows).  Float64 throughout, four kernels:
-//   prepare_kernel   C_h = W_h[Bbar,:] W_h[B,:]^{-1}, one workgroup per head: the d_h x d_h basis block
+//   prepare_kernel   C_h = W_h[Bbar,:] W_h[B,:]^{-1}, one workgroup per head (several when there are few heads:
+//                    each inverts for itself and takes a share of the rows): the d_h x d_h basis block
 //                    is inverted in place by Gauss-Jordan elimination with partial (row) pivoting (in
 //                    LDS up to d_h = 128, in the caller's workspace up to 256; the row interchanges are
 //                    undone as column interchanges at the end), then the d_c - d_h rows outside the
@@ -76,7 +77,8 @@ constexpr int kPrepLdsDh = 128;               // largest head width whose basis 
 constexpr int kPrepMaxDh = 256;               // largest head width at all (block in the workspace)
 constexpr int kPrepRows = 16;                 // rows of W_h[Bbar,:] staged per pass
 constexpr int kMaxCandidates = 256;
-constexpr int kMaxParts = 16;
+constexpr int kMaxParts = 64;                 // workgroups per head of the residual kernel, at most (heads x parts <= 1024: about four
+                                              // workgroups per compute unit, which cover one another's exposed load latency)
 
 struct PrepArgs {
     const void* W;
@@ -218,8 +220,12 @@ __global__ __launch_bounds__(kPrepThreads) void prepare_kernel(const PrepArgs a)
     __syncthreads();
 
     // ---- C_h = W_h[Bbar,:] A^{-1} ------------------------------------------------------------------
+    // With few heads a launch leaves most compute units idle, and the inversion above is one workgroup's
+    // latency whatever else runs: gridDim.y workgroups per head each invert the block for themselves (the
+    // same operations in the same order, so the same inverse bit for bit) and share out the row blocks of
+    // the product, which is a third of the kernel's time when one workgroup does all of them.
     const int K = a.d_c - n;
-    for (int r0 = 0; r0 < K; r0 += kPrepRows) {
+    for (int r0 = (int)blockIdx.y * kPrepRows; r0 < K; r0 += (int)gridDim.y * kPrepRows) {
         for (int e = t; e < kPrepRows * n; e += kPrepThreads) {
             const int i = e / n, c = e % n;
             const int r = r0 + i;
@@ -510,11 +516,18 @@ int launch_prepare(PrepArgs a, int batch, hipStream_t st)
     hipError_t err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (err != hipSuccess) return fail(BDA_EHIP, "bda_prepare_device: LDS size %zu: %s", lds, hipGetErrorString(err));
     const int per_launch = big ? batch : a.H;
+    // workgroups per head (the block in LDS only: a block in the workspace belongs to one workgroup): up to
+    // 64 per launch, at most one per row block.  More shorten a lone call a little further (16 heads x 16:
+    // 52.6 ms for a layer's offset searches against 54.8) but fill every compute unit with redundant
+    // inversions, and then calls on other streams no longer run beside this one (measured).
+    const int row_blocks = (a.d_c - n + kPrepRows - 1) / kPrepRows;
+    int per_head = big ? 1 : 64 / a.H;
+    per_head = per_head < 1 ? 1 : per_head > row_blocks ? (row_blocks < 1 ? 1 : row_blocks) : per_head;
     for (int h0 = 0; h0 < a.H; h0 += per_launch) {
         a.h0 = h0;
         const int heads = a.H - h0 < per_launch ? a.H - h0 : per_launch;
         if (big) hipLaunchKernelGGL((prepare_kernel<WT, CT, true>), dim3(heads), dim3(kPrepThreads), lds, st, a);
-        else hipLaunchKernelGGL((prepare_kernel<WT, CT, false>), dim3(heads), dim3(kPrepThreads), lds, st, a);
+        else hipLaunchKernelGGL((prepare_kernel<WT, CT, false>), dim3(heads, per_head), dim3(kPrepThreads), lds, st, a);
         if (int rc = check_launch("prepare kernel")) return rc;
     }
     return BDA_OK;

@@ -128,7 +128,7 @@ def test_prepare_device_ex_wide_heads(d_c, H, d_h, blocks):
     W, Wq, _ = _weights(d_c, H, d_h, 24, seed=500 + d_h)
     ws = None
     if blocks is not None:
-        ws = 1024 + 256 * ((2 * H * (1024 // H if 1024 // H < 16 else 16) * 8 + 255) // 256) + blocks * d_h * d_h * 8
+        ws = 1024 + 256 * ((2 * H * (1024 // H if 1024 // H < 64 else 64) * 8 + 255) // 256) + blocks * d_h * d_h * 8
     _check_against_oracle(W, d_c, H, d_h, wl.BF16, Wq, oracle.SIDE_Q, oracle.RESIDUAL_MIN, workspace_bytes=ws)
 
 

@@ -174,7 +174,7 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     # search somewhere to put the chosen window; no more than 256 candidate windows; d_h up to 256
     ex = lib.bda_prepare_device_ex
     need = lib.bda_prepare_device_workspace_bytes(64, 2, 16, 2, 0)
-    assert need == 1024 + 256 * ((2 * 2 * 16 * 8 + 255) // 256)
+    assert need == 1024 + 256 * ((2 * 2 * 64 * 8 + 255) // 256)      # flags + 2 candidates x 2 heads x 64 parts of a sum
     assert lib.bda_prepare_device_workspace_bytes(64, 2, 16, 0, 0) == 0 and lib.bda_prepare_device_workspace_bytes(64, 2, 64, 0, 0) == 0
     assert lib.bda_prepare_device_workspace_bytes(1024, 2, 256, 0, 0) == 1024 + 2 * 256 * 256 * 8
     assert ex(fake, 32, 3, 64, 2, 16, None, 0, 0, 0, 2, 0, fake, 32, None, 0, 1, fake, None, None, None, 0, None) == -1
