@@ -457,7 +457,7 @@ __global__ __launch_bounds__(kPrepThreads) void residual_kernel(const PrepArgs a
 }
 
 struct SelectArgs {
-    const double* partials;
+    double* partials;           // (a head's first part is overwritten with the root of its sum)
     const int* cand_singular;
     int* basis_offset_out;
     double* resid_out;           // NULL or 3 doubles: first window, last window, chosen window
@@ -465,24 +465,41 @@ struct SelectArgs {
     int offs[kMaxCandidates];
 };
 
-// One thread: the candidates in order, the heads in order, the parts in order.
-__global__ void select_kernel(const SelectArgs a)
+// One workgroup.  Every sum is taken by one thread in a fixed order - a head's parts in order, a candidate's
+// heads in order, the candidates in order - so the result does not depend on how the work is spread: first
+// a thread per (candidate, head) adds that head's parts and leaves the root in the first part's place (the
+// partial sums are the call's own workspace), then a thread per candidate takes the mean over the heads,
+// then one thread compares the candidates.
+constexpr int kSelectThreads = 256;
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(const SelectArgs a)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    __shared__ double s_mean[kMaxCandidates];
+    const int t = threadIdx.x;
+    if (a.partials) {
+        for (int e = t; e < a.n_cand * a.H; e += kSelectThreads) {
+            double* part = a.partials + (size_t)e * a.n_parts;
+            double s = 0.0;
+            for (int p = 0; p < a.n_parts; ++p) s += part[p];
+            part[0] = sqrt(s);
+        }
+    }
+    __syncthreads();
+    for (int ci = t; ci < a.n_cand; ci += kSelectThreads) {
+        double mean = 0.0;
+        if (a.partials) {
+            for (int h = 0; h < a.H; ++h) mean += a.partials[((size_t)ci * a.H + h) * a.n_parts];
+            mean /= a.H;
+        }
+        s_mean[ci] = mean;
+    }
+    __syncthreads();
+    if (t != 0) return;
     const double inf = __builtin_huge_val(), nan = __builtin_nan("");
     double best = inf, r_first = nan, r_last = nan;
     int best_off = -1;
     for (int ci = 0; ci < a.n_cand; ++ci) {
         const bool singular = a.cand_singular[ci] != 0;
-        double mean = 0.0;
-        if (a.partials) {
-            for (int h = 0; h < a.H; ++h) {
-                double s = 0.0;
-                for (int p = 0; p < a.n_parts; ++p) s += a.partials[((size_t)ci * a.H + h) * a.n_parts + p];
-                mean += sqrt(s);
-            }
-            mean /= a.H;
-        }
+        double mean = s_mean[ci];
         if (singular || mean != mean) mean = inf;
         if (a.offs[ci] == 0) r_first = mean;
         if (a.offs[ci] == a.d_c - a.d_h) r_last = mean;
@@ -623,7 +640,7 @@ int run_prepare(const PrepCall& c, const Plan& p, unsigned char* ws, hipStream_t
         s.partials = partials; s.cand_singular = flags; s.basis_offset_out = c.basis_offset_out; s.resid_out = c.resid_out;
         s.n_cand = p.n_cand; s.H = c.H; s.n_parts = p.n_parts; s.d_c = c.d_c; s.d_h = c.d_h;
         for (int i = 0; i < p.n_cand; ++i) s.offs[i] = p.offs[i];
-        hipLaunchKernelGGL(select_kernel, dim3(1), dim3(64), 0, st, s);
+        hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelectThreads), 0, st, s);
         if (int rc = check_launch("select kernel")) return rc;
     } else if (c.basis_offset_out) {
         hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(64), 0, st, c.basis_offset_out, 1, p.offs[0]);
