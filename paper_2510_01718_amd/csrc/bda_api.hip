@@ -312,6 +312,18 @@ void choose_super(GemmArgs& a, int max_slots, int bt, int bn)
 }
 
 // Common launcher.  a.A/B/D, lda/ldb/ldd, M, K, d_h, a_skip, ident and a_off[] are set by the caller.
+// Shape conditions of the lean streaming kernel (nothing in any stage depends on the lane: see
+// bda_gemm_plain.hpp) beyond those of the fast path: stages of 64 along K and along the window, whole
+// 256-column tiles, at least three stages per tile, sizes within the kernel's 24-bit column arithmetic.
+bool lean_kernel_applies(const GemmArgs& a, int G, const int64_t* group_cols)
+{
+    bool ok = a.K % 64 == 0 && a.K >= 64 && (!a.ident || a.d_h % 64 == 0) && a.d_h < (1 << 16);
+    for (int g = 0; g < G; ++g) ok = ok && group_cols[g] % 256 == 0 && group_cols[g] < (1 << 24);
+    const int id_width = (a.d_h % 256) == 0 ? 256 : a.d_h;                      // window columns a 256-column tile needs
+    const int id_stages = a.ident ? (id_width + 127) / 128 : 0;                 // double-width identity stages
+    return ok && a.K / 64 + id_stages >= 3;
+}
+
 int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_dtype, hipStream_t st)
 {
     int64_t N_total = 0;
@@ -362,13 +374,11 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
     // More than 128 tokens where the 32-column slices no longer fit: one round of the lean kernel's 64-token
     // tiles, where that kernel applies, beats 64-column slices with token tiles (N = 4096, 384 / 512 tokens:
     // 8.6 / 8.8 against 8.9 / 9.3 us).
-    bool lean64 = policy0 == 0 && !packed && a.M > kDecodeMaxT && fast && ident_tiles && a.K % 64 == 0 && a.K >= 64 &&
-                  (!a.ident || a.d_h % 64 == 0) && a.d_h < (1 << 16);
+    bool lean64 = policy0 == 0 && !packed && a.M > kDecodeMaxT && fast && ident_tiles && lean_kernel_applies(a, G, group_cols);
     {
         int64_t nt256 = 0;
-        for (int g = 0; g < G; ++g) { lean64 = lean64 && group_cols[g] % 256 == 0 && group_cols[g] < (1 << 24); nt256 += (group_cols[g] + 255) / 256; }
-        const int id_w = (a.d_h % 256) == 0 ? 256 : a.d_h;
-        lean64 = lean64 && a.K / 64 + (a.ident ? (id_w + 127) / 128 : 0) >= 3 && ((a.M + 63) / 64) * nt256 <= kNumXcd * kSlotsPerXcd;
+        for (int g = 0; g < G; ++g) nt256 += (group_cols[g] + 255) / 256;
+        lean64 = lean64 && ((a.M + 63) / 64) * nt256 <= kNumXcd * kSlotsPerXcd;
     }
     const bool wide_auto = a.M <= 64 ? n_slices128 >= 160 : (!fits32 && fits64 && !lean64);
     const bool small_T = a.M <= 64 || (!packed && a.M <= kDecodeMaxT * 8 && (fits32 || (fits64 && !lean64) || (policy0 == 5 && a.M <= kDecodeMaxT)));
@@ -405,9 +415,8 @@ int run_gemm(GemmArgs& a, int G, const int64_t* group_cols, int dtype, int out_d
         // stage depends on the lane: see bda_gemm_plain.hpp)?
         bool stream_ok = (a.K + kStreamSK - 1) / kStreamSK + n_stage_id >= kStreamNS && a.d_h < (1 << 16);
         for (int g = 0; g < G; ++g) stream_ok = stream_ok && group_cols[g] < (1 << 24);   // exact x % d_h by multiplication
-        bool plain = stream_ok && kStreamSK == 64 && kStreamNS == 2 && a.K % 64 == 0 && (!a.ident || a.d_h % 64 == 0)
-                     && a.K / 64 + n_stage_id_lean >= 3 && a.K >= 64 && policy != 3 && policy != 1;
-        for (int g = 0; g < G; ++g) plain = plain && group_cols[g] % 256 == 0;   // (window starts: multiples of 8, checked above)
+        const bool plain = stream_ok && kStreamSK == 64 && kStreamNS == 2 && lean_kernel_applies(a, G, group_cols)   // (window starts: multiples of 8, checked above)
+                           && policy != 3 && policy != 1;
         // Tile choice.  The lean kernel serves every tile count; its 128-token tile costs 0.53-0.56 of
         // its 256-token tile per round of tiles (measured), so the smaller tile is taken where it
         // needs less than 1 / 0.56 times the rounds.  Without the lean kernel: 256 x 256 streaming
